@@ -1,0 +1,224 @@
+"""Counter-based, device-independent generator of q / K / V test tensors.
+
+Recipe (per layer l, sequence b):
+  * q[b, h, :]            ~ N(0, 1), one vector per query head;
+  * K[b, hk, t, :], V[..] ~ N(0, 1) for every position of the padded cache;
+  * a seeded subset of round(frac * s_b) positions (at least one) per QUERY
+    head is made "pivotal": the K row of the head's KV head at that position
+    gets  3 * sqrt(d) * q / |q|  added (q before rounding to 16 bits), which
+    lifts its scaled score by about 3 |q| ~ 34, so pivots carry the softmax
+    mass.  With grouped queries each head of a group adds its own direction at
+    its own positions to the shared K head, in head order;
+  * everything is built in fp32 and rounded once (nearest-even) to fp16/bf16.
+
+Nothing here computes a score, a softmax or a selection.
+"""
+import dataclasses
+import math
+
+import numpy as np
+import torch
+from scipy.special import ndtri
+
+_M32 = 0xFFFFFFFF
+# odd multipliers below 2^31: products with a 32-bit value stay below 2^63,
+# so int64 tensors never overflow and CPU and GPU agree bit for bit
+_C1, _C2, _C3 = 0x7FEB352D, 0x2C1B3C6D, 0x297A2D39
+_STRIDE = 0x1E3779B1
+
+_T_Q, _T_K, _T_V, _T_PIVOT, _T_LEN = 0, 1, 2, 3, 4
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    L: int            # layers
+    B: int            # sequences
+    H: int            # query heads
+    Hkv: int          # KV heads
+    S_cap: int        # cache capacity (padded length)
+    N: int            # top-N
+    dtype: str        # "f16" | "bf16"
+    pivot_frac: float
+    seed: int
+    d: int = 128
+    len_range: tuple = None   # (lo, hi) inclusive for ragged batches, None = all S_cap
+
+    @property
+    def G(self):
+        return self.H // self.Hkv
+
+    def seq_lens(self):
+        if self.len_range is None:
+            return np.full(self.B, self.S_cap, dtype=np.int32)
+        lo, hi = self.len_range
+        rng = np.random.Generator(np.random.Philox(key=_unit_key(self.seed, _T_LEN, 0, 0, 0)))
+        return rng.integers(lo, hi + 1, size=self.B).astype(np.int32)
+
+    def replace(self, **kw):
+        return dataclasses.replace(self, **kw)
+
+
+CONFIGS = {
+    1: Workload("config1_mha_b1_s2048", L=1, B=1, H=8, Hkv=8, S_cap=2048, N=64, dtype="f16",
+                pivot_frac=0.01, seed=1001),
+    2: Workload("config2_llama2_7b_b8_s32768", L=32, B=8, H=32, Hkv=32, S_cap=32768, N=256,
+                dtype="f16", pivot_frac=0.005, seed=1002),
+    3: Workload("config3_llama3_8b_gqa_b16_s8192", L=32, B=16, H=32, Hkv=8, S_cap=8192, N=128,
+                dtype="bf16", pivot_frac=0.01, seed=1003),
+    4: Workload("config4_ragged_b64", L=1, B=64, H=32, Hkv=32, S_cap=16384, N=128, dtype="f16",
+                pivot_frac=0.01, seed=1004, len_range=(1024, 16384)),
+    5: Workload("config5_llama2_13b_b2_s65536", L=40, B=2, H=40, Hkv=40, S_cap=65536, N=512,
+                dtype="f16", pivot_frac=0.005, seed=1005),
+}
+
+
+def config(i, **overrides):
+    wl = CONFIGS[i]
+    return wl.replace(**overrides) if overrides else wl
+
+
+def torch_dtype(name):
+    return {"f16": torch.float16, "bf16": torch.bfloat16}[name]
+
+
+def as_bits(t):
+    """uint16 numpy view of a 16-bit floating torch tensor (copied to the host if needed)."""
+    return t.detach().contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def _mix_int(x):
+    x &= _M32
+    x = ((x ^ (x >> 16)) * _C1) & _M32
+    x = ((x ^ (x >> 15)) * _C2) & _M32
+    x = ((x ^ (x >> 13)) * _C3) & _M32
+    return x ^ (x >> 16)
+
+
+def _unit_key(seed, tensor, layer, b, head):
+    k = _mix_int(seed ^ 0x5BD1E995)
+    for part in (tensor, layer, b, head):
+        k = _mix_int(k ^ _mix_int(part + 0x9E3779B9))
+    return k
+
+
+def _mix_tensor(x):
+    """The same mixing on an int64 tensor whose values are below 2^32."""
+    x = ((x ^ (x >> 16)) * _C1) & _M32
+    x = ((x ^ (x >> 15)) * _C2) & _M32
+    x = ((x ^ (x >> 13)) * _C3) & _M32
+    return x ^ (x >> 16)
+
+
+_table_np = None
+_table_dev = {}
+
+
+def normal_table():
+    """65 536 standard-normal quantiles at (i + 1/2) / 65536, fp32, computed on the host."""
+    global _table_np
+    if _table_np is None:
+        u = (np.arange(65536, dtype=np.float64) + 0.5) / 65536.0
+        _table_np = ndtri(u).astype(np.float32)
+    return _table_np
+
+
+def _table_on(device):
+    key = str(device)
+    if key not in _table_dev:
+        _table_dev[key] = torch.from_numpy(normal_table()).to(device)
+    return _table_dev[key]
+
+
+def _fill_normal(keys, n, device):
+    """fp32 [len(keys), n]: element j of unit u is table[hash(keys[u], j) >> 16]."""
+    kt = torch.tensor(keys, dtype=torch.int64, device=device).unsqueeze(1)
+    ctr = torch.arange(n, dtype=torch.int64, device=device).unsqueeze(0)
+    x = (kt + ctr * _STRIDE) & _M32
+    x = _mix_tensor(x)
+    return _table_on(device)[x >> 16]
+
+
+def pivot_positions(wl, layer, b, h, s_b=None):
+    """Sorted distinct pivotal positions of query head h in sequence b."""
+    if s_b is None:
+        s_b = int(wl.seq_lens()[b])
+    n = max(1, int(math.floor(wl.pivot_frac * s_b + 0.5)))
+    n = min(n, s_b)
+    rng = np.random.Generator(np.random.Philox(key=_unit_key(wl.seed, _T_PIVOT, layer, b, h)))
+    return np.sort(rng.choice(s_b, size=n, replace=False)).astype(np.int64)
+
+
+def _q_f32(wl, layer):
+    keys = [_unit_key(wl.seed, _T_Q, layer, b, h) for b in range(wl.B) for h in range(wl.H)]
+    return _fill_normal(keys, wl.d, "cpu").reshape(wl.B, wl.H, wl.d)
+
+
+def _pivot_dirs(q_f32, d):
+    q64 = q_f32.numpy().astype(np.float64)
+    nrm = np.sqrt((q64 * q64).sum(axis=-1, keepdims=True))
+    return torch.from_numpy((3.0 * math.sqrt(d) * q64 / nrm).astype(np.float32))
+
+
+def gen_q(wl, layer, device="cpu"):
+    """q [B][H][d] in the storage dtype on `device`."""
+    return _q_f32(wl, layer).to(torch_dtype(wl.dtype)).to(device)
+
+
+def gen_kv_units(wl, layer, b, hks, rows, device="cpu"):
+    """K and V of sequence b for the KV heads in `hks`, first `rows` positions.
+
+    Returns (K, V), each [len(hks)][rows][d] in the storage dtype on `device`.
+    Pivots are placed only below the sequence's length; padded rows stay plain
+    N(0,1) values that a correct kernel must ignore."""
+    d, G = wl.d, wl.G
+    s_b = int(wl.seq_lens()[b])
+    dirs = _pivot_dirs(_q_f32(wl, layer), d)
+    out = []
+    for tensor in (_T_K, _T_V):
+        keys = [_unit_key(wl.seed, tensor, layer, b, hk) for hk in hks]
+        x = _fill_normal(keys, rows * d, device).reshape(len(hks) * rows, d)
+        if tensor == _T_K:
+            for g in range(G):   # head order fixes the order of overlapping fp32 adds
+                row_ids, add = [], []
+                for j, hk in enumerate(hks):
+                    h = hk * G + g
+                    pos = pivot_positions(wl, layer, b, h, s_b)
+                    pos = pos[pos < rows]
+                    row_ids.append(pos + j * rows)
+                    add.append(dirs[b, h].unsqueeze(0).expand(len(pos), d))
+                row_ids = torch.from_numpy(np.concatenate(row_ids)).to(device)
+                add = torch.cat(add, 0).to(device)
+                x.index_add_(0, row_ids, add)   # indices are distinct within one pass
+        out.append(x.to(torch_dtype(wl.dtype)).reshape(len(hks), rows, d))
+    return out[0], out[1]
+
+
+def gen_layer(wl, layer, device="cpu", k_out=None, v_out=None):
+    """Whole layer: (q [B][H][d], K [B][Hkv][S_cap][d], V same, seq_lens int32 [B] numpy).
+
+    K and V are written into k_out / v_out when given (any device, storage dtype)."""
+    dt = torch_dtype(wl.dtype)
+    shape = (wl.B, wl.Hkv, wl.S_cap, wl.d)
+    if k_out is None:
+        k_out = torch.empty(shape, dtype=dt, device=device)
+    if v_out is None:
+        v_out = torch.empty(shape, dtype=dt, device=device)
+    hks = list(range(wl.Hkv))
+    for b in range(wl.B):
+        k, v = gen_kv_units(wl, layer, b, hks, wl.S_cap, device)
+        k_out[b].copy_(k)
+        v_out[b].copy_(v)
+    return gen_q(wl, layer, device), k_out, v_out, wl.seq_lens()
+
+
+def gen_unit(wl, layer, b, h):
+    """Host regeneration of one (layer, sequence, query head) unit for the oracle.
+
+    Returns uint16 bit patterns (q [d], K [s_b][d], V [s_b][d]) of the rows the
+    unit may look at; identical to the corresponding slices of gen_layer."""
+    s_b = int(wl.seq_lens()[b])
+    hk = h // wl.G
+    k, v = gen_kv_units(wl, layer, b, [hk], s_b, "cpu")
+    q = gen_q(wl, layer, "cpu")[b, h]
+    return as_bits(q), as_bits(k[0]), as_bits(v[0])

@@ -1,0 +1,242 @@
+/*
+ * CPU oracle for KCache decode-step attention and its cache store.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It shares no code with the GPU path, is
+ * never linked into it, and must not be called from any product code path.
+ *
+ * What it computes (paper section 3.1, Table 1 rows "S~ = TopN(softmax(Q K^T /
+ * sqrt(d_h)))" and "A~ = S~ Part(V)", Figure 1 lower half, section 3.3 for the
+ * per-(sequence, head) granularity):
+ *
+ *   for every sequence b and query head i, over the s_b cached positions,
+ *     z[t]  = (q . K[t]) / sqrt(d_h)                  (scores)
+ *     p[t]  = exp(z[t] - max z) / sum_t exp(z[t] - max z)   (softmax over ALL t)
+ *     I     = the N positions with the largest p       (TopN)
+ *     out   = sum_{t in I} p[t] * V[t]                 (partial V, weighted)
+ *
+ * Readings taken where the paper is silent (all listed in the design notes):
+ *   - the kept weights are the full-context softmax values, not renormalised
+ *     (the formula is literally TopN applied to the softmax output);
+ *   - ordering is decided on z, which orders exactly like p in exact
+ *     arithmetic (exp is strictly increasing), lower position wins a tie;
+ *   - N_eff = min(N, s_b);
+ *   - d_h is the per-head dimension;
+ *   - grouped-query attention: query head i reads KV head i / (H / Hkv).
+ *
+ * Arithmetic: every stored 16-bit value is decoded exactly to double, all
+ * sums and the softmax are in double.  No blocking, fusion or reordering.
+ *
+ * Parity pins (tests/test_oracle_pins.py): softmax sums to one, shift
+ * invariance, N = s against a library attention routine, brute-force sort,
+ * uniform-score closed form, two-score logistic closed form, GQA by head
+ * repetition, ragged batch by independent calls, 16-bit decode against a
+ * library decode.  The no-renormalisation reading itself is "parity unpinned"
+ * by the paper: only the literal formula fixes it.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define KCO_F16 0
+#define KCO_BF16 1
+
+/* IEEE binary16 bit pattern -> double, exact. */
+static double kco_half_to_double(uint16_t h) {
+  int sign = (h >> 15) & 1;
+  int expo = (h >> 10) & 0x1f;
+  int frac = h & 0x3ff;
+  double v;
+  if (expo == 0) {
+    v = ldexp((double)frac, -24); /* subnormal: frac * 2^-10 * 2^-14 */
+  } else if (expo == 31) {
+    v = frac ? NAN : INFINITY;
+  } else {
+    v = ldexp((double)(frac + 1024), expo - 25); /* (1 + frac/1024) * 2^(expo-15) */
+  }
+  return sign ? -v : v;
+}
+
+/* bfloat16 bit pattern -> double, exact (sign, 8 exponent bits, 7 fraction bits). */
+static double kco_bf16_to_double(uint16_t h) {
+  int sign = (h >> 15) & 1;
+  int expo = (h >> 7) & 0xff;
+  int frac = h & 0x7f;
+  double v;
+  if (expo == 0) {
+    v = ldexp((double)frac, -133); /* frac * 2^-7 * 2^-126 */
+  } else if (expo == 255) {
+    v = frac ? NAN : INFINITY;
+  } else {
+    v = ldexp((double)(frac + 128), expo - 134); /* (1 + frac/128) * 2^(expo-127) */
+  }
+  return sign ? -v : v;
+}
+
+static double kco_decode(uint16_t bits, int dtype) {
+  return dtype == KCO_BF16 ? kco_bf16_to_double(bits) : kco_half_to_double(bits);
+}
+
+/* Exposed so the decode can be pinned against a library conversion. */
+void kcache_oracle_decode16(const uint16_t* bits, int64_t n, int dtype, double* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = kco_decode(bits[i], dtype);
+}
+
+typedef struct {
+  double z;
+  int32_t t;
+} kco_scored;
+
+/* Larger score first; equal scores: lower position first. */
+static int kco_cmp_scored(const void* a, const void* b) {
+  const kco_scored* x = (const kco_scored*)a;
+  const kco_scored* y = (const kco_scored*)b;
+  if (x->z > y->z) return -1;
+  if (x->z < y->z) return 1;
+  return (x->t > y->t) - (x->t < y->t);
+}
+
+static int kco_cmp_i32(const void* a, const void* b) {
+  int32_t x = *(const int32_t*)a, y = *(const int32_t*)b;
+  return (x > y) - (x < y);
+}
+
+/*
+ * One (sequence, query head) unit.
+ *   q      [d]      stored 16-bit values
+ *   K, V   [s][d]   rows of the shared KV head, position-major
+ *   out    [d]      double
+ *   idx    [N]      selected positions ascending, -1 beyond N_eff
+ *   w      [N]      their softmax weights, 0 beyond N_eff
+ *   z_out  [s]      optional (may be NULL): scaled scores
+ *   p_out  [s]      optional (may be NULL): full softmax
+ * Returns 0, or -1 on bad arguments / allocation failure.
+ */
+int kcache_oracle_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, int dtype,
+                       int32_t s, int32_t d, int32_t N, double* out, int32_t* idx, double* w,
+                       double* z_out, double* p_out) {
+  if (!q || !K || !V || !out || !idx || !w || s < 1 || d < 1 || N < 1) return -1;
+  double* z = (double*)malloc(sizeof(double) * (size_t)s);
+  double* p = (double*)malloc(sizeof(double) * (size_t)s);
+  double* qd = (double*)malloc(sizeof(double) * (size_t)d);
+  kco_scored* order = (kco_scored*)malloc(sizeof(kco_scored) * (size_t)s);
+  if (!z || !p || !qd || !order) {
+    free(z); free(p); free(qd); free(order);
+    return -1;
+  }
+  for (int32_t c = 0; c < d; ++c) qd[c] = kco_decode(q[c], dtype);
+
+  /* scores: z[t] = (q . K[t]) / sqrt(d_h) */
+  const double inv_sqrt_d = 1.0 / sqrt((double)d);
+  for (int32_t t = 0; t < s; ++t) {
+    double acc = 0.0;
+    for (int32_t c = 0; c < d; ++c)
+      acc += qd[c] * kco_decode(K[(size_t)t * d + c], dtype);
+    z[t] = acc * inv_sqrt_d;
+  }
+
+  /* softmax over all s positions */
+  double m = z[0];
+  for (int32_t t = 1; t < s; ++t)
+    if (z[t] > m) m = z[t];
+  double Z = 0.0;
+  for (int32_t t = 0; t < s; ++t) {
+    p[t] = exp(z[t] - m);
+    Z += p[t];
+  }
+  for (int32_t t = 0; t < s; ++t) p[t] /= Z;
+
+  /* TopN: order all positions by (score descending, position ascending) */
+  for (int32_t t = 0; t < s; ++t) {
+    order[t].z = z[t];
+    order[t].t = t;
+  }
+  qsort(order, (size_t)s, sizeof(kco_scored), kco_cmp_scored);
+  int32_t n_eff = N < s ? N : s;
+  for (int32_t j = 0; j < n_eff; ++j) idx[j] = order[j].t;
+  qsort(idx, (size_t)n_eff, sizeof(int32_t), kco_cmp_i32);
+  for (int32_t j = n_eff; j < N; ++j) idx[j] = -1;
+
+  /* weighted sum of the selected V rows, weights NOT renormalised */
+  for (int32_t c = 0; c < d; ++c) out[c] = 0.0;
+  for (int32_t j = 0; j < N; ++j) {
+    if (j >= n_eff) {
+      w[j] = 0.0;
+      continue;
+    }
+    int32_t t = idx[j];
+    w[j] = p[t];
+    for (int32_t c = 0; c < d; ++c) out[c] += p[t] * kco_decode(V[(size_t)t * d + c], dtype);
+  }
+
+  if (z_out) memcpy(z_out, z, sizeof(double) * (size_t)s);
+  if (p_out) memcpy(p_out, p, sizeof(double) * (size_t)s);
+  free(z); free(p); free(qd); free(order);
+  return 0;
+}
+
+/*
+ * One layer, whole batch.
+ *   q         [B][H][d]
+ *   K, V      [B][Hkv][S_cap][d]   (V read from ordinary host memory)
+ *   seq_lens  [B]   1 <= s_b <= S_cap
+ *   out       [B][H][d] double;  idx [B][H][N];  w [B][H][N]
+ *   nthreads  units are independent; they are split over this many threads
+ *             (the only parallelism).  <= 1 runs serially.
+ * Returns 0, or -1 on bad arguments.
+ */
+int kcache_oracle_decode(const uint16_t* q, const uint16_t* K, const uint16_t* V, int dtype,
+                         int32_t B, int32_t H, int32_t Hkv, int32_t S_cap, int32_t d,
+                         const int32_t* seq_lens, int32_t N, double* out, int32_t* idx, double* w,
+                         int nthreads) {
+  if (!q || !K || !V || !seq_lens || !out || !idx || !w) return -1;
+  if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || S_cap < 1 || d < 1 || N < 1) return -1;
+  for (int32_t b = 0; b < B; ++b)
+    if (seq_lens[b] < 1 || seq_lens[b] > S_cap) return -1;
+  const int32_t G = H / Hkv;
+  int status = 0;
+  int64_t units = (int64_t)B * H;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 1 ? nthreads : 1)
+  for (int64_t u = 0; u < units; ++u) {
+    int32_t b = (int32_t)(u / H), h = (int32_t)(u % H);
+    int32_t hk = h / G;
+    size_t kv_off = ((size_t)b * Hkv + hk) * (size_t)S_cap * d;
+    int rc = kcache_oracle_unit(q + (size_t)u * d, K + kv_off, V + kv_off, dtype, seq_lens[b], d, N,
+                                out + (size_t)u * d, idx + (size_t)u * N, w + (size_t)u * N, NULL,
+                                NULL);
+    if (rc != 0) {
+#pragma omp atomic write
+      status = -1;
+    }
+  }
+  return status;
+}
+
+/*
+ * Cache store (Figure 1 upper half and caption: every layer's K states are
+ * pushed to the HBM cache, V states end up in CPU memory; in decode the new
+ * token's states are appended the same way).
+ *   k_new, v_new  [B][T][Hkv][d]  token-major, as a projection produces them
+ *   k_cache, v_cache [B][Hkv][S_cap][d]
+ *   pos [B]  first position written for each sequence; pos[b] + T <= S_cap
+ * Pure data movement; bits are copied unchanged.
+ */
+int kcache_oracle_store(uint16_t* k_cache, uint16_t* v_cache, const uint16_t* k_new,
+                        const uint16_t* v_new, const int32_t* pos, int32_t B, int32_t T,
+                        int32_t Hkv, int32_t S_cap, int32_t d) {
+  if (!k_cache || !v_cache || !k_new || !v_new || !pos) return -1;
+  if (B < 1 || T < 1 || Hkv < 1 || S_cap < 1 || d < 1) return -1;
+  for (int32_t b = 0; b < B; ++b)
+    if (pos[b] < 0 || (int64_t)pos[b] + T > S_cap) return -1;
+  for (int32_t b = 0; b < B; ++b)
+    for (int32_t t = 0; t < T; ++t)
+      for (int32_t hk = 0; hk < Hkv; ++hk)
+        for (int32_t c = 0; c < d; ++c) {
+          size_t src = (((size_t)b * T + t) * Hkv + hk) * d + c;
+          size_t dst = (((size_t)b * Hkv + hk) * S_cap + (size_t)(pos[b] + t)) * d + c;
+          k_cache[dst] = k_new[src];
+          v_cache[dst] = v_new[src];
+        }
+  return 0;
+}
