@@ -1,0 +1,197 @@
+/*
+ * libkcache: KCache decode-step attention for one MI355X (gfx950).
+ *
+ * The method (paper section 3.1, Figure 1, Table 1 "KCache MHA" rows): the K
+ * cache of every layer stays in HBM, the V cache lives in CPU memory.  A decode
+ * step scores the query against the whole K cache, takes the softmax over all
+ * positions, keeps the N largest entries per (sequence, head), pulls only those
+ * N rows of V across the host link and returns their weighted sum.
+ *
+ * Conventions of this C ABI
+ *   - plain pointers and sizes only; "dev" = device (HBM) pointer, "host" =
+ *     pinned, device-mapped host pointer (hipHostMalloc / torch pin_memory);
+ *   - every call returns KC_OK (0) or a negative kc_status; the text of the
+ *     last failure of a context is available from kcache_last_error();
+ *   - arguments are validated on the host before anything is enqueued; nothing
+ *     aborts or throws across the boundary;
+ *   - calls enqueue work on the caller's HIP stream and do not synchronise with
+ *     the host unless stated; the caller owns q / K / V / out memory, the
+ *     library owns only its workspace, its side streams and events;
+ *   - a context is bound to one device and must not be used from two host
+ *     threads at once.
+ */
+#ifndef KCACHE_H_
+#define KCACHE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kc_ctx kc_ctx;
+
+typedef enum { KC_F16 = 0, KC_BF16 = 1 } kc_dtype;
+
+/* How the selected V rows cross the host link (Figure 1 "VCache Pull"; the
+ * paper does not say which mechanism its engine uses):
+ *   ZEROCOPY  the accumulate kernel reads the rows straight out of the mapped
+ *             host cache (no host involvement, fully asynchronous);
+ *   STAGED    indices go to the host, host threads pack the rows into a pinned
+ *             staging buffer, one async copy brings them to HBM, a kernel
+ *             accumulates.  This mode blocks the calling host thread until the
+ *             indices have arrived. */
+typedef enum { KC_GATHER_ZEROCOPY = 0, KC_GATHER_STAGED = 1 } kc_gather_mode;
+
+typedef enum {
+  KC_OK = 0,
+  KC_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, H % Hkv != 0 ...     */
+  KC_ERR_UNSUPPORTED = -2, /* head_dim other than 128, group size not in {1,2,4,8}  */
+  KC_ERR_NOT_PINNED = -3,  /* v_host is not device-mapped host memory                */
+  KC_ERR_WORKSPACE = -4,   /* workspace could not be (re)allocated                   */
+  KC_ERR_HIP = -5,         /* a HIP runtime call failed; see kcache_last_error       */
+  KC_ERR_DEVICE_CHECK = -6 /* a kernel found pos / seq_lens outside the cache        */
+} kc_status;
+
+/* One layer's cache.  Both buffers are owned by the caller.
+ * Element (b, hk, t, c) of either cache is at ((b*Hkv + hk)*S_cap + t)*d + c, so
+ * the K rows of one (sequence, KV head) form one contiguous stream and every V
+ * row is one contiguous 256-byte read (section 3.1: K in HBM, V in CPU memory). */
+typedef struct {
+  void* k_dev;    /* dev   [B][Hkv][S_cap][d], 16-bit elements                       */
+  void* v_host;   /* host  [B][Hkv][S_cap][d], same layout, pinned + mapped          */
+  int32_t B;      /* sequences                                                       */
+  int32_t Hkv;    /* KV heads                                                        */
+  int32_t S_cap;  /* capacity in positions                                           */
+  int32_t d;      /* head dimension d_h; must be 128                                 */
+  int32_t dtype;  /* kc_dtype of q, K, V                                             */
+} kc_layer_cache;
+
+/* Identifiers for kcache_profile_read. */
+typedef enum {
+  KC_KERNEL_KSCAN = 0,   /* scores q.K^T / sqrt(d_h) over the context (HBM bound)    */
+  KC_KERNEL_SELECT = 1,  /* softmax statistics + top-N select                        */
+  KC_KERNEL_GATHER = 2,  /* V row pull + weighted sum (host-link bound)              */
+  KC_KERNEL_STORE_K = 3, /* cache store, K half                                      */
+  KC_KERNEL_STORE_V = 4, /* cache store, V half (device to host)                     */
+  KC_KERNEL_COUNT = 5
+} kc_kernel_id;
+
+/* Integer options for kcache_set_option. */
+typedef enum {
+  KC_OPT_PIPELINE_PARTS = 0, /* decode: split the (sequence, KV head) units into this
+                                many parts so the V pull of one part overlaps the K
+                                scan of the next; 0 = choose automatically            */
+  KC_OPT_PROFILE = 1,        /* 1: bracket every kernel with HIP events (see
+                                kcache_profile_read); 0: off (default)                */
+  KC_OPT_STAGED_THREADS = 2  /* host threads packing rows in KC_GATHER_STAGED mode    */
+} kc_option;
+
+/* Create a context on `device` (a HIP device ordinal) with a workspace of at
+ * least workspace_bytes_hint bytes (0 is fine: the workspace grows on demand,
+ * which synchronises the device once).  *out is set only on success. */
+int kcache_create(kc_ctx** out, int device, size_t workspace_bytes_hint);
+
+/* Wait for the context's side streams, free its workspace.  NULL is accepted. */
+int kcache_destroy(kc_ctx* ctx);
+
+/* Bytes of device workspace a decode call of this shape needs (fp32 scores
+ * [B][H][S_cap] plus index / weight buffers [B][H][N]).  0 on invalid sizes. */
+size_t kcache_workspace_bytes(int32_t B, int32_t H, int32_t S_cap, int32_t N);
+
+/* Text of the last error recorded in this context ("" if none).  The pointer
+ * stays valid until the next failing call on the context.  ctx == NULL returns
+ * the text of the last failing kcache_create of the calling thread. */
+const char* kcache_last_error(kc_ctx* ctx);
+
+int kcache_set_option(kc_ctx* ctx, int32_t option, int64_t value);
+
+/* Host-only shape check shared by the two calls below; touches no GPU state.
+ * H and N are ignored when H == 0 (store-only check). */
+int kcache_check_shapes(const kc_layer_cache* cache, int32_t H, int32_t N);
+
+/*
+ * Cache store (Figure 1 upper half and caption: each layer pushes its K and V
+ * states; V is then copied to CPU memory asynchronously; in decode the new
+ * token's states are appended the same way).  Writes T new tokens per sequence
+ * at positions [pos[b], pos[b] + T).
+ *   k_new_dev, v_new_dev  dev [B][T][Hkv][d], cache dtype (token-major)
+ *   pos_dev               dev int32 [B]; the kernel skips (and flags, see
+ *                         kcache_device_check) any row outside [0, S_cap)
+ *   T                     >= 1
+ *   stream                hipStream_t on which k_new / v_new / pos are ready
+ *   done_event            optional hipEvent_t, recorded when the V rows have
+ *                         been written to host memory
+ * K rows are written into cache->k_dev on `stream`.  V rows are written to
+ * cache->v_host by a kernel on an internal side stream ordered after `stream`;
+ * later kcache_decode_attention calls on the same context wait for it on the
+ * device.  The caller must keep v_new_dev alive until done_event (or a
+ * kcache_synchronize) has completed.
+ */
+int kcache_prefill_store(kc_ctx* ctx, const kc_layer_cache* cache, const void* k_new_dev,
+                         const void* v_new_dev, const int32_t* pos_dev, int32_t T, void* stream,
+                         void* done_event);
+
+/*
+ * KCache attention for one layer and one decode step (section 3.1; Table 1 rows
+ * S~ = TopN(softmax(Q K^T / sqrt(d_h))) and A~ = S~ Part(V); section 3.3 for
+ * the per-(sequence, head) granularity).
+ *   q_dev         dev [B][H][d], cache dtype
+ *   H             query heads; H % Hkv == 0 and H / Hkv in {1, 2, 4, 8}; query
+ *                 head h reads KV head h / (H / Hkv)
+ *   seq_lens_dev  dev int32 [B], 1 <= s_b <= S_cap, counts the current token,
+ *                 whose K and V rows the caller has already stored
+ *   N             >= 1; N_eff = min(N, s_b) positions are kept
+ *   out_dev       dev fp32 [B][H][d]:  sum over the kept positions of
+ *                 softmax(z)[t] * V[t]; the weights are the full-context
+ *                 softmax values (not renormalised over the kept set)
+ *   idx_out_dev   optional dev int32 [B][H][N]: kept positions, ascending,
+ *                 -1 beyond N_eff; equal scores are broken towards the lower
+ *                 position
+ *   w_out_dev     optional dev fp32 [B][H][N]: matching weights, 0 beyond N_eff
+ *   gather_mode   kc_gather_mode
+ *   stream        hipStream_t; all results are complete in stream order
+ * Scores and softmax are fp32; the selection is made on the fp32 scores.
+ */
+int kcache_decode_attention(kc_ctx* ctx, const kc_layer_cache* cache, const void* q_dev, int32_t H,
+                            const int32_t* seq_lens_dev, int32_t N, float* out_dev,
+                            int32_t* idx_out_dev, float* w_out_dev, int32_t gather_mode,
+                            void* stream);
+
+/* Block until everything this context has enqueued (side streams included) is done. */
+int kcache_synchronize(kc_ctx* ctx);
+
+/* Synchronises, then reports whether any kernel since the last check met a
+ * pos / seq_lens value outside the cache: KC_OK or KC_ERR_DEVICE_CHECK. */
+int kcache_device_check(kc_ctx* ctx);
+
+/* Per-kernel timing, active while KC_OPT_PROFILE is 1.  Synchronises, then
+ * returns the sum of HIP-event durations (ms) and the number of launches of
+ * `kernel` since the last kcache_profile_reset. */
+int kcache_profile_read(kc_ctx* ctx, int32_t kernel, double* total_ms, int64_t* launches);
+int kcache_profile_reset(kc_ctx* ctx);
+
+/*
+ * Bandwidth probes: the denominators the roofline fractions are quoted against.
+ * read:  a streaming kernel sums `bytes` (multiple of 16) starting at `ptr`,
+ *        device memory or mapped host memory, `iters` times; *gbps = bytes *
+ *        iters / time.
+ * rows:  the same kernel shape as the V pull: `n_rows` rows of 256 bytes at
+ *        pseudo-random row offsets inside [ptr, ptr + bytes).
+ * copy:  hipMemcpyAsync(dst, src, bytes) `iters` times (pinned H2D / D2H peak).
+ * All three synchronise the stream.
+ */
+int kcache_probe_read(kc_ctx* ctx, const void* ptr, size_t bytes, int32_t iters, void* stream,
+                      double* gbps);
+int kcache_probe_rows(kc_ctx* ctx, const void* ptr, size_t bytes, int64_t n_rows, int32_t iters,
+                      void* stream, double* gbps);
+int kcache_probe_copy(kc_ctx* ctx, void* dst, const void* src, size_t bytes, int32_t iters,
+                      void* stream, double* gbps);
+
+const char* kcache_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KCACHE_H_ */

@@ -1,0 +1,682 @@
+// Host side of libkcache: argument validation, workspace, streams and events,
+// the pipelining of K scan against V pull, and the C ABI of include/kcache.h.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <condition_variable>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <functional>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "../../include/kcache.h"
+#include "kc_internal.h"
+
+namespace {
+
+thread_local std::string g_create_error;
+
+// Minimal persistent worker pool for the staged gather (host threads pack the
+// selected V rows into one pinned buffer).
+class Pool {
+ public:
+  explicit Pool(int n) {
+    for (int i = 0; i < n; ++i) workers_.emplace_back([this] { run(); });
+  }
+  ~Pool() {
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      stop_ = true;
+    }
+    cv_.notify_all();
+    for (auto& t : workers_) t.join();
+  }
+  int size() const { return (int)workers_.size(); }
+  // Calls fn(i) for i in [0, n), spread over the workers and the caller.
+  void parallel_for(int64_t n, const std::function<void(int64_t)>& fn) {
+    if (n <= 0) return;
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      fn_ = &fn;
+      next_.store(0);
+      total_ = n;
+      active_ = (int)workers_.size();
+      ++epoch_;
+    }
+    cv_.notify_all();
+    drain();
+    std::unique_lock<std::mutex> l(mu_);
+    done_cv_.wait(l, [this] { return active_ == 0; });
+    fn_ = nullptr;
+  }
+
+ private:
+  void drain() {
+    for (;;) {
+      int64_t i = next_.fetch_add(1);
+      if (i >= total_) break;
+      (*fn_)(i);
+    }
+  }
+  void run() {
+    uint64_t seen = 0;
+    for (;;) {
+      {
+        std::unique_lock<std::mutex> l(mu_);
+        cv_.wait(l, [&] { return stop_ || epoch_ != seen; });
+        if (stop_) return;
+        seen = epoch_;
+      }
+      drain();
+      {
+        std::lock_guard<std::mutex> g(mu_);
+        if (--active_ == 0) done_cv_.notify_all();
+      }
+    }
+  }
+  std::vector<std::thread> workers_;
+  std::mutex mu_;
+  std::condition_variable cv_, done_cv_;
+  const std::function<void(int64_t)>* fn_ = nullptr;
+  std::atomic<int64_t> next_{0};
+  int64_t total_ = 0;
+  int active_ = 0;
+  uint64_t epoch_ = 0;
+  bool stop_ = false;
+};
+
+struct ProfRec {
+  int kernel;
+  hipEvent_t a, b;
+};
+
+constexpr int kMaxParts = 64;
+
+}  // namespace
+
+struct kc_ctx {
+  int device = 0;
+  hipStream_t side = nullptr;        // select + V pull of a part, while the next part is scanned
+  hipStream_t store_side = nullptr;  // V half of the cache store
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_store = nullptr, ev_last = nullptr;
+  hipEvent_t ev_part[kMaxParts] = {};
+  bool store_pending = false, have_last = false;
+  void* ws = nullptr;
+  size_t ws_bytes = 0;
+  int* flags = nullptr;  // [0] device-check bits, [16] probe sink
+  std::string err;
+  int parts = 0, profile = 0, staged_threads = 8;
+  std::vector<ProfRec> pending;
+  std::vector<hipEvent_t> free_events;
+  double prof_ms[KC_KERNEL_COUNT] = {};
+  int64_t prof_n[KC_KERNEL_COUNT] = {};
+  // staged gather
+  Pool* pool = nullptr;
+  int32_t* h_idx = nullptr;
+  void* h_rows = nullptr;
+  void* d_rows = nullptr;
+  size_t staged_rows = 0;
+};
+
+namespace {
+
+int fail(kc_ctx* c, int status, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c)
+    c->err = buf;
+  else
+    g_create_error = buf;
+  return status;
+}
+
+#define KC_HIP(c, call)                                                                    \
+  do {                                                                                     \
+    hipError_t e_ = (call);                                                                \
+    if (e_ != hipSuccess)                                                                  \
+      return fail((c), KC_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_));         \
+  } while (0)
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = true;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) prev = -1;
+    if (prev != dev) ok = hipSetDevice(dev) == hipSuccess;
+  }
+  ~DeviceGuard() {
+    int cur = -1;
+    if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+  }
+};
+
+size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+bool sizes_ok(int64_t B, int64_t H, int64_t S_cap, int64_t N) {
+  return B >= 1 && H >= 1 && S_cap >= 1 && N >= 1 && B * H < (1ll << 31) &&
+         B * H * S_cap < (1ll << 40) && B * H * N < (1ll << 36);
+}
+
+hipEvent_t get_event(kc_ctx* c) {
+  if (!c->free_events.empty()) {
+    hipEvent_t e = c->free_events.back();
+    c->free_events.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+// Brackets one kernel launch with events while profiling is on.
+struct KernelTimer {
+  kc_ctx* c;
+  int id;
+  hipStream_t st;
+  hipEvent_t a = nullptr;
+  KernelTimer(kc_ctx* c_, int id_, hipStream_t st_) : c(c_), id(id_), st(st_) {
+    if (c->profile && (a = get_event(c))) (void)hipEventRecord(a, st);
+  }
+  ~KernelTimer() {
+    if (!a) return;
+    hipEvent_t b = get_event(c);
+    if (!b) {
+      c->free_events.push_back(a);
+      return;
+    }
+    (void)hipEventRecord(b, st);
+    c->pending.push_back({id, a, b});
+  }
+};
+
+int collect_profile(kc_ctx* c) {
+  for (auto& r : c->pending) {
+    float ms = 0.f;
+    KC_HIP(c, hipEventSynchronize(r.b));
+    KC_HIP(c, hipEventElapsedTime(&ms, r.a, r.b));
+    c->prof_ms[r.kernel] += ms;
+    c->prof_n[r.kernel] += 1;
+    c->free_events.push_back(r.a);
+    c->free_events.push_back(r.b);
+  }
+  c->pending.clear();
+  return KC_OK;
+}
+
+int ensure_workspace(kc_ctx* c, size_t bytes) {
+  if (bytes <= c->ws_bytes) return KC_OK;
+  KC_HIP(c, hipDeviceSynchronize());
+  if (c->ws) (void)hipFree(c->ws);
+  c->ws = nullptr;
+  c->ws_bytes = 0;
+  hipError_t e = hipMalloc(&c->ws, bytes);
+  if (e != hipSuccess)
+    return fail(c, KC_ERR_WORKSPACE, "workspace of %zu bytes: %s", bytes, hipGetErrorString(e));
+  c->ws_bytes = bytes;
+  return KC_OK;
+}
+
+int ensure_staged(kc_ctx* c, size_t rows) {
+  if (!c->pool || c->pool->size() != std::max(0, c->staged_threads - 1)) {
+    delete c->pool;
+    c->pool = new Pool(std::max(0, c->staged_threads - 1));
+  }
+  if (rows <= c->staged_rows) return KC_OK;
+  KC_HIP(c, hipDeviceSynchronize());
+  if (c->h_idx) (void)hipHostFree(c->h_idx);
+  if (c->h_rows) (void)hipHostFree(c->h_rows);
+  if (c->d_rows) (void)hipFree(c->d_rows);
+  c->h_idx = nullptr;
+  c->h_rows = c->d_rows = nullptr;
+  c->staged_rows = 0;
+  KC_HIP(c, hipHostMalloc((void**)&c->h_idx, rows * sizeof(int32_t), hipHostMallocDefault));
+  KC_HIP(c, hipHostMalloc(&c->h_rows, rows * kc::kRowBytes, hipHostMallocDefault));
+  hipError_t e = hipMalloc(&c->d_rows, rows * kc::kRowBytes);
+  if (e != hipSuccess)
+    return fail(c, KC_ERR_WORKSPACE, "staging of %zu rows: %s", rows, hipGetErrorString(e));
+  c->staged_rows = rows;
+  return KC_OK;
+}
+
+// Device-visible address of pinned, mapped host memory, or an error.
+int mapped_host_pointer(kc_ctx* c, void* host, void** dev) {
+  hipPointerAttribute_t attr;
+  memset(&attr, 0, sizeof attr);
+  hipError_t e = hipPointerGetAttributes(&attr, host);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(c, KC_ERR_NOT_PINNED, "v_host %p is not known to HIP (%s): it must be pinned, "
+                "mapped host memory", host, hipGetErrorString(e));
+  }
+  if (attr.type != hipMemoryTypeHost)
+    return fail(c, KC_ERR_NOT_PINNED, "v_host %p has memory type %d, expected pinned host memory",
+                host, (int)attr.type);
+  e = hipHostGetDevicePointer(dev, host, 0);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(c, KC_ERR_NOT_PINNED, "v_host %p is not mapped into the device: %s", host,
+                hipGetErrorString(e));
+  }
+  return KC_OK;
+}
+
+int shape_status(const kc_layer_cache* cache, int32_t H, int32_t N, const char** why) {
+  *why = "";
+  if (!cache) return *why = "cache is NULL", KC_ERR_INVALID_ARG;
+  if (cache->B < 1 || cache->Hkv < 1 || cache->S_cap < 1)
+    return *why = "B, Hkv and S_cap must be positive", KC_ERR_INVALID_ARG;
+  if (cache->dtype != KC_F16 && cache->dtype != KC_BF16)
+    return *why = "dtype must be KC_F16 or KC_BF16", KC_ERR_INVALID_ARG;
+  if (cache->d != kc::kHeadDim) return *why = "head dimension must be 128", KC_ERR_UNSUPPORTED;
+  if ((int64_t)cache->B * cache->Hkv * cache->S_cap >= (1ll << 40))
+    return *why = "cache too large", KC_ERR_INVALID_ARG;
+  if (H == 0) return KC_OK;
+  if (H < 1 || N < 1) return *why = "H and N must be positive", KC_ERR_INVALID_ARG;
+  if (H % cache->Hkv != 0) return *why = "H must be a multiple of Hkv", KC_ERR_INVALID_ARG;
+  const int G = H / cache->Hkv;
+  if (G != 1 && G != 2 && G != 4 && G != 8)
+    return *why = "group size H/Hkv must be 1, 2, 4 or 8", KC_ERR_UNSUPPORTED;
+  if (!sizes_ok(cache->B, H, cache->S_cap, N)) return *why = "sizes too large", KC_ERR_INVALID_ARG;
+  return KC_OK;
+}
+
+int pick_parts(const kc_ctx* c, int kv_units, size_t k_bytes) {
+  int p = c->parts;
+  if (p <= 0) p = k_bytes >= ((size_t)256 << 20) ? 4 : 1;
+  p = std::min(p, std::min(kv_units, kMaxParts));
+  return std::max(p, 1);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* kcache_version(void) { return "kcache-gfx950 0.1"; }
+
+size_t kcache_workspace_bytes(int32_t B, int32_t H, int32_t S_cap, int32_t N) {
+  if (!sizes_ok(B, H, S_cap, N)) return 0;
+  const size_t units = (size_t)B * H;
+  return round256(units * S_cap * sizeof(float)) + 2 * round256(units * N * sizeof(int32_t));
+}
+
+int kcache_check_shapes(const kc_layer_cache* cache, int32_t H, int32_t N) {
+  const char* why;
+  return shape_status(cache, H, N, &why);
+}
+
+int kcache_create(kc_ctx** out, int device, size_t workspace_bytes_hint) {
+  if (!out) return fail(nullptr, KC_ERR_INVALID_ARG, "out is NULL");
+  int count = 0;
+  hipError_t e = hipGetDeviceCount(&count);
+  if (e != hipSuccess || count < 1) {
+    (void)hipGetLastError();
+    return fail(nullptr, KC_ERR_HIP, "no HIP device available (%s)",
+                e == hipSuccess ? "device count is 0" : hipGetErrorString(e));
+  }
+  if (device < 0 || device >= count)
+    return fail(nullptr, KC_ERR_INVALID_ARG, "device %d outside [0, %d)", device, count);
+  DeviceGuard g(device);
+  if (!g.ok) return fail(nullptr, KC_ERR_HIP, "hipSetDevice(%d) failed", device);
+  kc_ctx* c = new kc_ctx();
+  c->device = device;
+  auto bail = [&](const char* what, hipError_t err) {
+    std::string msg = std::string(what) + ": " + hipGetErrorString(err);
+    kcache_destroy(c);
+    return fail(nullptr, KC_ERR_HIP, "%s", msg.c_str());
+  };
+  if ((e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking)) != hipSuccess)
+    return bail("hipStreamCreate", e);
+  if ((e = hipStreamCreateWithFlags(&c->store_side, hipStreamNonBlocking)) != hipSuccess)
+    return bail("hipStreamCreate", e);
+  hipEvent_t* evs[] = {&c->ev_fork, &c->ev_join, &c->ev_store, &c->ev_last};
+  for (auto* ev : evs)
+    if ((e = hipEventCreateWithFlags(ev, hipEventDisableTiming)) != hipSuccess)
+      return bail("hipEventCreate", e);
+  for (int i = 0; i < kMaxParts; ++i)
+    if ((e = hipEventCreateWithFlags(&c->ev_part[i], hipEventDisableTiming)) != hipSuccess)
+      return bail("hipEventCreate", e);
+  if ((e = hipMalloc((void**)&c->flags, 256)) != hipSuccess) return bail("hipMalloc", e);
+  if ((e = hipMemset(c->flags, 0, 256)) != hipSuccess) return bail("hipMemset", e);
+  if (workspace_bytes_hint) {
+    int rc = ensure_workspace(c, workspace_bytes_hint);
+    if (rc != KC_OK) {
+      std::string msg = c->err;
+      kcache_destroy(c);
+      return fail(nullptr, rc, "%s", msg.c_str());
+    }
+  }
+  *out = c;
+  return KC_OK;
+}
+
+int kcache_destroy(kc_ctx* c) {
+  if (!c) return KC_OK;
+  DeviceGuard g(c->device);
+  (void)hipDeviceSynchronize();
+  delete c->pool;
+  for (auto& r : c->pending) {
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  for (auto e : c->free_events) (void)hipEventDestroy(e);
+  hipEvent_t evs[] = {c->ev_fork, c->ev_join, c->ev_store, c->ev_last};
+  for (auto e : evs)
+    if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_part)
+    if (e) (void)hipEventDestroy(e);
+  if (c->side) (void)hipStreamDestroy(c->side);
+  if (c->store_side) (void)hipStreamDestroy(c->store_side);
+  if (c->ws) (void)hipFree(c->ws);
+  if (c->flags) (void)hipFree(c->flags);
+  if (c->h_idx) (void)hipHostFree(c->h_idx);
+  if (c->h_rows) (void)hipHostFree(c->h_rows);
+  if (c->d_rows) (void)hipFree(c->d_rows);
+  delete c;
+  return KC_OK;
+}
+
+const char* kcache_last_error(kc_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+int kcache_set_option(kc_ctx* c, int32_t option, int64_t value) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  switch (option) {
+    case KC_OPT_PIPELINE_PARTS:
+      if (value < 0 || value > kMaxParts)
+        return fail(c, KC_ERR_INVALID_ARG, "pipeline parts must be in [0, %d]", kMaxParts);
+      c->parts = (int)value;
+      return KC_OK;
+    case KC_OPT_PROFILE:
+      c->profile = value != 0;
+      return KC_OK;
+    case KC_OPT_STAGED_THREADS:
+      if (value < 1 || value > 256)
+        return fail(c, KC_ERR_INVALID_ARG, "staged threads must be in [1, 256]");
+      c->staged_threads = (int)value;
+      return KC_OK;
+    default:
+      return fail(c, KC_ERR_INVALID_ARG, "unknown option %d", option);
+  }
+}
+
+int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_new_dev,
+                         const void* v_new_dev, const int32_t* pos_dev, int32_t T, void* stream,
+                         void* done_event) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  const char* why;
+  int rc = shape_status(cache, 0, 0, &why);
+  if (rc != KC_OK) return fail(c, rc, "kcache_prefill_store: %s", why);
+  if (!cache->k_dev || !cache->v_host || !k_new_dev || !v_new_dev || !pos_dev)
+    return fail(c, KC_ERR_INVALID_ARG, "kcache_prefill_store: NULL pointer argument");
+  if (T < 1 || T > cache->S_cap)
+    return fail(c, KC_ERR_INVALID_ARG, "kcache_prefill_store: T = %d outside [1, S_cap = %d]", T,
+                cache->S_cap);
+  DeviceGuard g(c->device);
+  if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  void* v_map = nullptr;
+  if ((rc = mapped_host_pointer(c, cache->v_host, &v_map)) != KC_OK) return rc;
+
+  hipStream_t st = (hipStream_t)stream;
+  const kc::Shape sh{cache->B, 0, cache->Hkv, cache->S_cap, 0, cache->dtype};
+  // V first: the side stream starts as soon as the inputs are ready on `st`
+  KC_HIP(c, hipEventRecord(c->ev_fork, st));
+  KC_HIP(c, hipStreamWaitEvent(c->store_side, c->ev_fork, 0));
+  {
+    KernelTimer t(c, KC_KERNEL_STORE_V, c->store_side);
+    KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, pos_dev, T, c->flags, c->store_side));
+  }
+  KC_HIP(c, hipEventRecord(c->ev_store, c->store_side));
+  c->store_pending = true;
+  if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, c->store_side));
+  {
+    KernelTimer t(c, KC_KERNEL_STORE_K, st);
+    KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, pos_dev, T, c->flags, st));
+  }
+  return KC_OK;
+}
+
+int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* q_dev, int32_t H,
+                            const int32_t* seq_lens_dev, int32_t N, float* out_dev,
+                            int32_t* idx_out_dev, float* w_out_dev, int32_t gather_mode,
+                            void* stream) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  const char* why;
+  int rc = shape_status(cache, H == 0 ? -1 : H, N, &why);
+  if (rc != KC_OK) return fail(c, rc, "kcache_decode_attention: %s", why);
+  if (!cache->k_dev || !cache->v_host || !q_dev || !seq_lens_dev || !out_dev)
+    return fail(c, KC_ERR_INVALID_ARG, "kcache_decode_attention: NULL pointer argument");
+  if (gather_mode != KC_GATHER_ZEROCOPY && gather_mode != KC_GATHER_STAGED)
+    return fail(c, KC_ERR_INVALID_ARG, "kcache_decode_attention: unknown gather mode %d",
+                gather_mode);
+  DeviceGuard g(c->device);
+  if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  void* v_map = nullptr;
+  if ((rc = mapped_host_pointer(c, cache->v_host, &v_map)) != KC_OK) return rc;
+
+  const int B = cache->B, Hkv = cache->Hkv, S_cap = cache->S_cap, G = H / Hkv;
+  const size_t units = (size_t)B * H;
+  if ((rc = ensure_workspace(c, kcache_workspace_bytes(B, H, S_cap, N))) != KC_OK) return rc;
+  const bool staged = gather_mode == KC_GATHER_STAGED;
+  if (staged && (rc = ensure_staged(c, units * N)) != KC_OK) return rc;
+
+  char* wsp = static_cast<char*>(c->ws);
+  float* z = reinterpret_cast<float*>(wsp);
+  wsp += round256(units * S_cap * sizeof(float));
+  int32_t* idx = idx_out_dev ? idx_out_dev : reinterpret_cast<int32_t*>(wsp);
+  wsp += round256(units * N * sizeof(int32_t));
+  float* w = w_out_dev ? w_out_dev : reinterpret_cast<float*>(wsp);
+
+  hipStream_t st = (hipStream_t)stream;
+  const kc::Shape sh{B, H, Hkv, S_cap, N, cache->dtype};
+  const int kv_units = B * Hkv;
+  const int parts = pick_parts(c, kv_units, (size_t)kv_units * S_cap * kc::kRowBytes);
+
+  // the workspace and the V rows must be free of earlier work of this context
+  if (c->have_last) KC_HIP(c, hipStreamWaitEvent(st, c->ev_last, 0));
+  if (c->store_pending) {
+    KC_HIP(c, hipStreamWaitEvent(st, c->ev_store, 0));
+    c->store_pending = false;
+  }
+
+  auto part_range = [&](int p, int* kv0, int* cnt) {
+    *kv0 = (int)((int64_t)kv_units * p / parts);
+    *cnt = (int)((int64_t)kv_units * (p + 1) / parts) - *kv0;
+  };
+
+  if (!staged) {
+    const bool overlap = parts > 1;
+    hipStream_t tail = overlap ? c->side : st;
+    if (overlap) {
+      KC_HIP(c, hipEventRecord(c->ev_fork, st));
+      KC_HIP(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+    }
+    for (int p = 0; p < parts; ++p) {
+      int kv0, cnt;
+      part_range(p, &kv0, &cnt);
+      {
+        KernelTimer t(c, KC_KERNEL_KSCAN, st);
+        KC_HIP(c, kc::launch_kscan(sh, q_dev, cache->k_dev, seq_lens_dev, z, kv0, cnt, c->flags,
+                                   st));
+      }
+      if (overlap) {
+        KC_HIP(c, hipEventRecord(c->ev_part[p], st));
+        KC_HIP(c, hipStreamWaitEvent(c->side, c->ev_part[p], 0));
+      }
+      {
+        KernelTimer t(c, KC_KERNEL_SELECT, tail);
+        KC_HIP(c, kc::launch_select(sh, z, seq_lens_dev, idx, w, kv0 * G, cnt * G, tail));
+      }
+      {
+        KernelTimer t(c, KC_KERNEL_GATHER, tail);
+        KC_HIP(c, kc::launch_gather(sh, v_map, idx, w, out_dev, kv0 * G, cnt * G, 0, tail));
+      }
+    }
+    if (overlap) {
+      KC_HIP(c, hipEventRecord(c->ev_join, c->side));
+      KC_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
+    }
+  } else {
+    // All scans and selects are enqueued up front; the host then packs part p
+    // while the GPU is still scanning the later parts.
+    for (int p = 0; p < parts; ++p) {
+      int kv0, cnt;
+      part_range(p, &kv0, &cnt);
+      {
+        KernelTimer t(c, KC_KERNEL_KSCAN, st);
+        KC_HIP(c, kc::launch_kscan(sh, q_dev, cache->k_dev, seq_lens_dev, z, kv0, cnt, c->flags,
+                                   st));
+      }
+      {
+        KernelTimer t(c, KC_KERNEL_SELECT, st);
+        KC_HIP(c, kc::launch_select(sh, z, seq_lens_dev, idx, w, kv0 * G, cnt * G, st));
+      }
+      const size_t off = (size_t)kv0 * G * N, n = (size_t)cnt * G * N;
+      KC_HIP(c, hipMemcpyAsync(c->h_idx + off, idx + off, n * sizeof(int32_t),
+                               hipMemcpyDeviceToHost, st));
+      KC_HIP(c, hipEventRecord(c->ev_part[p], st));
+    }
+    const char* v_base = static_cast<const char*>(cache->v_host);
+    char* rows = static_cast<char*>(c->h_rows);
+    const int32_t* h_idx = c->h_idx;
+    for (int p = 0; p < parts; ++p) {
+      int kv0, cnt;
+      part_range(p, &kv0, &cnt);
+      KC_HIP(c, hipEventSynchronize(c->ev_part[p]));
+      const int64_t u_first = (int64_t)kv0 * G, u_count = (int64_t)cnt * G;
+      std::function<void(int64_t)> pack = [&](int64_t i) {
+        const int64_t u = u_first + i;
+        const int64_t b = u / H, hk = (u % H) / G;
+        const char* src = v_base + ((b * Hkv + hk) * (int64_t)S_cap) * kc::kRowBytes;
+        for (int j = 0; j < N; ++j) {
+          const int32_t t = h_idx[u * N + j];
+          if (t < 0) break;
+          memcpy(rows + (u * N + j) * kc::kRowBytes, src + (int64_t)t * kc::kRowBytes,
+                 kc::kRowBytes);
+        }
+      };
+      c->pool->parallel_for(u_count, pack);
+      const size_t off = (size_t)u_first * N * kc::kRowBytes, n = (size_t)u_count * N * kc::kRowBytes;
+      if (p == 0) {
+        KC_HIP(c, hipEventRecord(c->ev_fork, st));  // side must not run ahead of earlier work
+        KC_HIP(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+      }
+      KC_HIP(c, hipMemcpyAsync(static_cast<char*>(c->d_rows) + off, rows + off, n,
+                               hipMemcpyHostToDevice, c->side));
+      {
+        KernelTimer t(c, KC_KERNEL_GATHER, c->side);
+        KC_HIP(c, kc::launch_gather(sh, c->d_rows, idx, w, out_dev, (int)u_first, (int)u_count, 1,
+                                    c->side));
+      }
+    }
+    KC_HIP(c, hipEventRecord(c->ev_join, c->side));
+    KC_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
+  }
+  KC_HIP(c, hipEventRecord(c->ev_last, st));
+  c->have_last = true;
+  return KC_OK;
+}
+
+int kcache_synchronize(kc_ctx* c) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  DeviceGuard g(c->device);
+  KC_HIP(c, hipStreamSynchronize(c->side));
+  KC_HIP(c, hipStreamSynchronize(c->store_side));
+  if (c->have_last) KC_HIP(c, hipEventSynchronize(c->ev_last));
+  return KC_OK;
+}
+
+int kcache_device_check(kc_ctx* c) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  DeviceGuard g(c->device);
+  KC_HIP(c, hipDeviceSynchronize());
+  int host_flags = 0;
+  KC_HIP(c, hipMemcpy(&host_flags, c->flags, sizeof(int), hipMemcpyDeviceToHost));
+  if (host_flags == 0) return KC_OK;
+  KC_HIP(c, hipMemset(c->flags, 0, sizeof(int)));
+  return fail(c, KC_ERR_DEVICE_CHECK, "device check:%s%s",
+              (host_flags & kc::kFlagBadSeqLen) ? " seq_lens outside [1, S_cap]" : "",
+              (host_flags & kc::kFlagBadPos) ? " store position outside [0, S_cap)" : "");
+}
+
+int kcache_profile_read(kc_ctx* c, int32_t kernel, double* total_ms, int64_t* launches) {
+  if (!c || kernel < 0 || kernel >= KC_KERNEL_COUNT || !total_ms || !launches)
+    return KC_ERR_INVALID_ARG;
+  DeviceGuard g(c->device);
+  int rc = collect_profile(c);
+  if (rc != KC_OK) return rc;
+  *total_ms = c->prof_ms[kernel];
+  *launches = c->prof_n[kernel];
+  return KC_OK;
+}
+
+int kcache_profile_reset(kc_ctx* c) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  DeviceGuard g(c->device);
+  int rc = collect_profile(c);
+  if (rc != KC_OK) return rc;
+  for (int i = 0; i < KC_KERNEL_COUNT; ++i) {
+    c->prof_ms[i] = 0;
+    c->prof_n[i] = 0;
+  }
+  return KC_OK;
+}
+
+static int timed_loop(kc_ctx* c, hipStream_t st, int iters, size_t bytes_per_iter, double* gbps,
+                      const std::function<hipError_t()>& body) {
+  hipEvent_t a = nullptr, b = nullptr;
+  KC_HIP(c, hipEventCreate(&a));
+  KC_HIP(c, hipEventCreate(&b));
+  hipError_t e = body();  // warm-up, untimed
+  if (e == hipSuccess) e = hipEventRecord(a, st);
+  for (int i = 0; i < iters && e == hipSuccess; ++i) e = body();
+  if (e == hipSuccess) e = hipEventRecord(b, st);
+  if (e == hipSuccess) e = hipEventSynchronize(b);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  if (e != hipSuccess) return fail(c, KC_ERR_HIP, "probe failed: %s", hipGetErrorString(e));
+  *gbps = ms > 0 ? (double)bytes_per_iter * iters / (ms * 1e-3) / 1e9 : 0.0;
+  return KC_OK;
+}
+
+int kcache_probe_read(kc_ctx* c, const void* ptr, size_t bytes, int32_t iters, void* stream,
+                      double* gbps) {
+  if (!c || !ptr || !gbps || bytes < 16 || iters < 1) return KC_ERR_INVALID_ARG;
+  DeviceGuard g(c->device);
+  hipStream_t st = (hipStream_t)stream;
+  uint32_t* sink = reinterpret_cast<uint32_t*>(c->flags + 16);
+  bytes &= ~(size_t)15;
+  return timed_loop(c, st, iters, bytes, gbps,
+                    [&] { return kc::launch_probe_read(ptr, bytes, sink, st); });
+}
+
+int kcache_probe_rows(kc_ctx* c, const void* ptr, size_t bytes, int64_t n_rows, int32_t iters,
+                      void* stream, double* gbps) {
+  if (!c || !ptr || !gbps || bytes < (size_t)kc::kRowBytes || n_rows < 1 || iters < 1)
+    return KC_ERR_INVALID_ARG;
+  DeviceGuard g(c->device);
+  hipStream_t st = (hipStream_t)stream;
+  uint32_t* sink = reinterpret_cast<uint32_t*>(c->flags + 16);
+  const size_t total_rows = bytes / kc::kRowBytes;
+  return timed_loop(c, st, iters, (size_t)n_rows * kc::kRowBytes, gbps,
+                    [&] { return kc::launch_probe_rows(ptr, total_rows, n_rows, sink, st); });
+}
+
+int kcache_probe_copy(kc_ctx* c, void* dst, const void* src, size_t bytes, int32_t iters,
+                      void* stream, double* gbps) {
+  if (!c || !dst || !src || !gbps || bytes < 1 || iters < 1) return KC_ERR_INVALID_ARG;
+  DeviceGuard g(c->device);
+  hipStream_t st = (hipStream_t)stream;
+  return timed_loop(c, st, iters, bytes, gbps,
+                    [&] { return hipMemcpyAsync(dst, src, bytes, hipMemcpyDefault, st); });
+}
+
+}  // extern "C"

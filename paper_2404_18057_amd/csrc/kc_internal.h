@@ -1,0 +1,56 @@
+// Internal launch interface between the host side of libkcache and its kernels.
+// Nothing here is part of the C ABI (include/kcache.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kc {
+
+constexpr int kHeadDim = 128;           // d_h: one row = 128 16-bit values = 256 bytes
+constexpr int kRowBytes = 256;
+constexpr int kScanRowsPerBlock = 1024;  // K rows scored by one workgroup
+constexpr int kSelectThreads = 512;
+
+// 16-byte load that tells the caches the data will not be used again.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const uint4* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// bits of the device-check word
+constexpr int kFlagBadSeqLen = 1;
+constexpr int kFlagBadPos = 2;
+
+struct Shape {
+  int B, H, Hkv, S_cap, N, dtype;
+};
+
+// Scores z[b][h][t] = (q[b][h] . K[b][h/G][t]) / sqrt(d_h) for the KV units
+// [kv0, kv0 + kv_count) (a KV unit is one (sequence, KV head)); all G query
+// heads of a unit are scored from one pass over its K rows.
+hipError_t launch_kscan(const Shape& sh, const void* q, const void* k, const int32_t* seq_lens,
+                        float* z, int kv0, int kv_count, int* flags, hipStream_t st);
+
+// Softmax statistics over all s_b scores and exact top-N_eff selection for the
+// query units [u0, u0 + count) (unit = b*H + h).  Writes ascending positions
+// and their softmax weights, padded with -1 / 0 up to N.
+hipError_t launch_select(const Shape& sh, const float* z, const int32_t* seq_lens, int32_t* idx,
+                         float* w, int u0, int count, hipStream_t st);
+
+// out[b][h][:] = sum_j w[j] * V[b][h/G][idx[j]][:].  `v` is the mapped host
+// cache (or, with packed = 1, a device buffer holding row j of unit u at
+// (u*N + j)*d).
+hipError_t launch_gather(const Shape& sh, const void* v, const int32_t* idx, const float* w,
+                         float* out, int u0, int count, int packed, hipStream_t st);
+
+// Copy rows of src [B][T][Hkv][d] to dst [B][Hkv][S_cap][d] at pos[b] + t.
+hipError_t launch_store(const Shape& sh, const void* src, void* dst, const int32_t* pos, int T,
+                        int* flags, hipStream_t st);
+
+hipError_t launch_probe_read(const void* ptr, size_t bytes, uint32_t* sink, hipStream_t st);
+hipError_t launch_probe_rows(const void* ptr, size_t total_rows, int64_t n_rows, uint32_t* sink,
+                             hipStream_t st);
+
+}  // namespace kc

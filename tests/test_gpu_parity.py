@@ -1,0 +1,299 @@
+"""GPU parity: libkcache (through the C ABI) against the CPU oracle, unit by unit."""
+import numpy as np
+import pytest
+import torch
+
+import kcache_inputs as ki
+import oracle
+from harness import (build_layer, check_unit, dtype_code, oracle_unit, pinned_like, run_and_check,
+                     sample_units)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def kc():
+    import paper_2404_18057_amd as kc
+    return kc
+
+
+@pytest.fixture(scope="module")
+def ctx(kc):
+    c = kc.Context(0)
+    yield c
+    c.close()
+
+
+def bits_t(a, dtype=torch.float16):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dtype)
+
+
+def manual_case(kc, ctx, q, K, V, lens, N, dtype=torch.float16, parts=0, gather_mode=0):
+    """q [B][H][d], K/V [B][Hkv][S][d] float arrays -> GPU result + oracle result."""
+    qt, kt, vt = bits_t(q, dtype), bits_t(K, dtype), bits_t(V, dtype)
+    B, H, d = qt.shape
+    k_dev = kt.to(DEV)
+    v_host = pinned_like(vt)
+    v_host.copy_(vt)
+    cache = kc.LayerCache(k_dev, v_host)
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    idx = torch.empty((B, H, N), dtype=torch.int32, device=DEV)
+    w = torch.empty((B, H, N), dtype=torch.float32, device=DEV)
+    ctx.set_pipeline_parts(parts)
+    out = ctx.decode_attention(cache, qt.to(DEV), lens_dev, N, idx_out=idx, w_out=w,
+                               gather_mode=gather_mode)
+    torch.cuda.synchronize()
+    ctx.set_pipeline_parts(0)
+    ctx.device_check()
+    code = oracle.F16 if dtype == torch.float16 else oracle.BF16
+    return (out.cpu().numpy(), idx.cpu().numpy(), w.cpu().numpy(),
+            (ki.as_bits(qt), ki.as_bits(kt), ki.as_bits(vt), code))
+
+
+def check_manual(res, lens, N, G=1):
+    out, idx, w, (qb, kb, vb, code) = res
+    B, H, _ = qb.shape
+    for b in range(B):
+        s = int(lens[b])
+        for h in range(H):
+            r = oracle.decode_unit(qb[b, h], kb[b, h // G, :s], vb[b, h // G, :s], code, N,
+                                   want_scores=True)
+            r["v"] = oracle.decode16(vb[b, h // G, :s], code)
+            check_unit(r, N, out[b, h], idx[b, h], w[b, h], tag="manual (%d,%d)" % (b, h))
+
+
+# ------------------------------------------------------------------ named configurations
+def test_config1_every_unit(kc, ctx):
+    wl = ki.config(1)
+    cache, q, lens, _, _ = build_layer(ctx, wl, 0)
+    same, n, _ = run_and_check(ctx, wl, 0, cache, q, lens, sample_units(wl, 10 ** 9))
+    assert n == 8
+
+
+@pytest.mark.parametrize("parts", [1, 3])
+def test_config1_pipelined_parts_give_identical_results(kc, ctx, parts):
+    wl = ki.config(1)
+    cache, q, lens, _, _ = build_layer(ctx, wl, 0)
+    ctx.set_pipeline_parts(1)
+    _, _, base = run_and_check(ctx, wl, 0, cache, q, lens, [(0, 0)])
+    ctx.set_pipeline_parts(parts)
+    _, _, got = run_and_check(ctx, wl, 0, cache, q, lens, sample_units(wl, 10 ** 9))
+    ctx.set_pipeline_parts(0)
+    for a, b in zip(base, got):
+        assert np.array_equal(a, b)
+
+
+def test_config3_shape_gqa_bf16_two_layers(kc, ctx):
+    # full per-layer shape of config 3 (B 16, 32 query / 8 KV heads, 8192, N 128, bf16)
+    wl = ki.config(3)
+    for layer in (0, wl.L - 1):
+        cache, q, lens, _, _ = build_layer(ctx, wl, layer)
+        run_and_check(ctx, wl, layer, cache, q, lens, sample_units(wl, 48, seed=layer))
+        del cache
+
+
+def test_config2_shape_two_layers(kc, ctx):
+    # full per-layer shape of config 2 (B 8, 32 heads, 32768, N 256, fp16)
+    wl = ki.config(2)
+    for layer in (0, wl.L - 1):
+        cache, q, lens, _, _ = build_layer(ctx, wl, layer, chunk_T=8192)
+        run_and_check(ctx, wl, layer, cache, q, lens, sample_units(wl, 32, seed=layer))
+        del cache
+
+
+def test_config5_shape_two_layers(kc, ctx):
+    # full per-layer shape of config 5 (B 2, 40 heads, 65536, N 512, fp16)
+    wl = ki.config(5)
+    for layer in (0, wl.L - 1):
+        cache, q, lens, _, _ = build_layer(ctx, wl, layer, chunk_T=16384)
+        run_and_check(ctx, wl, layer, cache, q, lens, sample_units(wl, 24, seed=layer))
+        del cache
+
+
+@pytest.mark.parametrize("frac", [0.001, 0.01, 0.05])
+def test_config4_ragged_sweeps(kc, ctx, frac):
+    # 64 ragged sequences, N swept over {32..512}, pivot fraction over {0.1, 1, 5} %
+    wl = ki.config(4, pivot_frac=frac)
+    cache, q, lens, _, _ = build_layer(ctx, wl, 0)
+    for N in (32, 64, 128, 256, 512):
+        run_and_check(ctx, wl, 0, cache, q, lens, sample_units(wl, 24, seed=N), N=N)
+
+
+# ------------------------------------------------------------------ edge cases
+def test_uniform_scores_break_ties_towards_lower_positions(kc, ctx):
+    rng = np.random.default_rng(0)
+    B, H, S, d, N = 2, 2, 700, 128, 37
+    q = rng.standard_normal((B, H, d))
+    K = np.tile(rng.standard_normal((B, H, 1, d)), (1, 1, S, 1))     # identical rows
+    V = rng.standard_normal((B, H, S, d))
+    lens = [700, 123]
+    out, idx, w, _ = res = manual_case(kc, ctx, q, K, V, lens, N)
+    for b in range(B):
+        for h in range(H):
+            assert idx[b, h].tolist() == list(range(N))
+            assert np.allclose(w[b, h], 1.0 / lens[b], rtol=1e-5)
+    check_manual(res, lens, N)
+
+
+def test_partial_ties_at_the_boundary(kc, ctx):
+    # 3 distinct score levels; the boundary falls inside the middle level
+    rng = np.random.default_rng(1)
+    S, d, N = 300, 128, 50
+    base = rng.standard_normal(d)
+    q = base[None, None, :]
+    level = rng.choice([0.0, 0.5, 1.0], size=S, p=[0.6, 0.3, 0.1])
+    K = (level[:, None] * base[None, :] / 4.0)[None, None]
+    V = rng.standard_normal((1, 1, S, d))
+    out, idx, w, _ = res = manual_case(kc, ctx, q, K, V, [S], N)
+    hi = np.flatnonzero(level == 1.0)
+    mid = np.flatnonzero(level == 0.5)
+    want = sorted(hi.tolist() + mid[:N - len(hi)].tolist())
+    assert len(hi) < N < len(hi) + len(mid)
+    assert idx[0, 0].tolist() == want
+    check_manual(res, [S], N)
+
+
+@pytest.mark.parametrize("S_cap,lens,N", [
+    (1, [1], 4),                 # a single cached position
+    (1000, [1000, 1, 63], 64),   # capacity not a multiple of any tile, N > s
+    (1029, [1029, 1025], 1),     # N = 1, ragged tail of one row past a block
+    (4100, [4100, 2049], 4100),  # N = s: full attention
+])
+def test_small_shapes_and_ragged_tails(kc, ctx, S_cap, lens, N):
+    rng = np.random.default_rng(S_cap)
+    B, H, d = len(lens), 3, 128
+    q = rng.standard_normal((B, H, d))
+    K = rng.standard_normal((B, H, S_cap, d))
+    V = rng.standard_normal((B, H, S_cap, d))
+    for b in range(B):          # padding must be ignored: make it attractive
+        K[b, :, lens[b]:] = 4 * q[b][:, None, :]
+    res = manual_case(kc, ctx, q, K, V, lens, N)
+    check_manual(res, lens, N)
+
+
+@pytest.mark.parametrize("G", [2, 8])
+def test_other_group_sizes(kc, ctx, G):
+    rng = np.random.default_rng(G)
+    B, Hkv, S, d, N = 2, 2, 777, 128, 20
+    H = Hkv * G
+    q = rng.standard_normal((B, H, d))
+    K = rng.standard_normal((B, Hkv, S, d))
+    V = rng.standard_normal((B, Hkv, S, d))
+    res = manual_case(kc, ctx, q, K, V, [777, 400], N, dtype=torch.bfloat16)
+    check_manual(res, [777, 400], N, G=G)
+
+
+def test_staged_gather_matches_zero_copy(kc, ctx):
+    wl = ki.config(1)
+    cache, q, lens, _, _ = build_layer(ctx, wl, 0)
+    _, _, a = run_and_check(ctx, wl, 0, cache, q, lens, sample_units(wl, 10 ** 9))
+    for threads in (1, 4):
+        ctx.set_staged_threads(threads)
+        _, _, b = run_and_check(ctx, wl, 0, cache, q, lens, sample_units(wl, 10 ** 9),
+                                gather_mode=kc.GATHER_STAGED)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+
+
+def test_results_are_deterministic(kc, ctx):
+    wl = ki.config(4, B=8)
+    cache, q, lens, _, _ = build_layer(ctx, wl, 0)
+    _, _, a = run_and_check(ctx, wl, 0, cache, q, lens, [(0, 0)])
+    _, _, b = run_and_check(ctx, wl, 0, cache, q, lens, [(7, 31)])
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+# ------------------------------------------------------------------ cache store
+def test_prefill_store_matches_oracle_bit_for_bit(kc, ctx):
+    rng = np.random.default_rng(5)
+    B, T, Hkv, d, S_cap = 3, 37, 5, 128, 100
+    k_new = bits_t(rng.standard_normal((B, T, Hkv, d)))
+    v_new = bits_t(rng.standard_normal((B, T, Hkv, d)))
+    pos = np.array([0, 63, 11], np.int32)
+    k_cache = torch.full((B, Hkv, S_cap, d), 9.0, dtype=torch.float16)
+    v_cache = torch.full((B, Hkv, S_cap, d), -9.0, dtype=torch.float16)
+    k_ref, v_ref = ki.as_bits(k_cache).copy(), ki.as_bits(v_cache).copy()
+    oracle.store(k_ref, v_ref, ki.as_bits(k_new), ki.as_bits(v_new), pos)
+    k_dev = k_cache.to(DEV)
+    v_host = pinned_like(v_cache)
+    v_host.copy_(v_cache)
+    cache = kc.LayerCache(k_dev, v_host)
+    done = torch.cuda.Event()
+    ctx.prefill_store(cache, k_new.to(DEV), v_new.to(DEV), torch.from_numpy(pos).to(DEV),
+                      done_event=done)
+    done.synchronize()
+    assert np.array_equal(ki.as_bits(v_host), v_ref)
+    torch.cuda.synchronize()
+    assert np.array_equal(ki.as_bits(k_dev), k_ref)
+    ctx.device_check()
+
+
+def test_append_one_token_then_decode_sees_it(kc, ctx):
+    # decode flow: the new token's K/V rows are stored (T = 1), then attention runs
+    wl = ki.config(1, S_cap=600, N=16, seed=5)
+    q, k, v, _ = ki.gen_layer(wl, 0, DEV)
+    s0 = 555
+    k_cache = k.clone()
+    v_host = pinned_like(v)
+    v_host.copy_(v)
+    cache = kc.LayerCache(k_cache, v_host)
+    # the appended token is a strong match for every head's query, with a marker V row
+    k_tok = (q.float() * 3).to(q.dtype).reshape(wl.B, 1, wl.Hkv, wl.d).contiguous()
+    v_tok = torch.full((wl.B, 1, wl.Hkv, wl.d), 2.5, dtype=q.dtype, device=DEV)
+    pos = torch.full((wl.B,), s0, dtype=torch.int32, device=DEV)
+    ctx.prefill_store(cache, k_tok, v_tok, pos)
+    lens = torch.full((wl.B,), s0 + 1, dtype=torch.int32, device=DEV)
+    idx = torch.empty((wl.B, wl.H, wl.N), dtype=torch.int32, device=DEV)
+    w = torch.empty((wl.B, wl.H, wl.N), dtype=torch.float32, device=DEV)
+    out = ctx.decode_attention(cache, q, lens, wl.N, idx_out=idx, w_out=w)
+    torch.cuda.synchronize()
+    kb, vb = ki.as_bits(k_cache), ki.as_bits(v_host)
+    qb = ki.as_bits(q)
+    for h in range(wl.H):
+        assert s0 in idx[0, h].tolist()
+        r = oracle.decode_unit(qb[0, h], kb[0, h, :s0 + 1], vb[0, h, :s0 + 1], dtype_code(wl),
+                               wl.N, want_scores=True)
+        r["v"] = oracle.decode16(vb[0, h, :s0 + 1], dtype_code(wl))
+        check_unit(r, wl.N, out[0, h].cpu().numpy(), idx[0, h].cpu().numpy(),
+                   w[0, h].cpu().numpy(), tag="append head %d" % h)
+
+
+def test_generator_bits_are_identical_on_cpu_and_gpu(kc):
+    for cfg, layer in ((1, 0), (3, 5)):
+        wl = ki.config(cfg).replace(B=2) if cfg == 3 else ki.config(cfg)
+        q, k, v, _ = ki.gen_layer(wl, layer, DEV)
+        qc, kc_, vc, _ = ki.gen_layer(wl, layer, "cpu")
+        assert torch.equal(q.cpu(), qc) and torch.equal(k.cpu(), kc_) and torch.equal(v.cpu(), vc)
+
+
+# ------------------------------------------------------------------ error paths (every kernel still exits normally)
+def test_bad_arguments_are_reported_not_fatal(kc, ctx):
+    wl = ki.config(1)
+    q, k, v, lens = ki.gen_layer(wl, 0, DEV)
+    v_pin = pinned_like(v)
+    cache = kc.LayerCache(k, v_pin)
+    lens_dev = torch.from_numpy(lens).to(DEV)
+    with pytest.raises(kc.KCacheError) as e:
+        ctx.decode_attention(cache, q, lens_dev, 0)
+    assert e.value.status == -1
+    # pageable (not pinned) V cache
+    bad = kc.LayerCache(k, v.cpu())
+    with pytest.raises(kc.KCacheError) as e:
+        ctx.decode_attention(bad, q, lens_dev, 8)
+    assert e.value.status == -3
+    # a sequence length outside the cache is clamped by the kernels and flagged
+    wrong = torch.tensor([wl.S_cap + 5], dtype=torch.int32, device=DEV)
+    ctx.decode_attention(cache, q, wrong, 8)
+    with pytest.raises(kc.KCacheError) as e:
+        ctx.device_check()
+    assert e.value.status == -6
+    ctx.device_check()      # the flag is cleared by the failing check
+    # a store position outside the cache is skipped and flagged
+    k_new = k[:, :, :4].permute(0, 2, 1, 3).contiguous()
+    pos = torch.tensor([wl.S_cap - 2], dtype=torch.int32, device=DEV)
+    ctx.prefill_store(cache, k_new, k_new, pos)
+    with pytest.raises(kc.KCacheError) as e:
+        ctx.device_check()
+    assert e.value.status == -6
