@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""KCache decode-attention benchmark on one MI355X.
+
+A step is one decode step of the whole hot path over one batch: for every
+layer, the new token's K/V rows are stored (T = 1) and kcache_decode_attention
+runs (K scan over the full context, softmax, top-N, V pull from pinned host
+memory, weighted sum).  All inputs are synthetic, seeded, and already resident
+(K in HBM, V in pinned host memory) when the timed region starts.
+
+Prints one JSON line: tokens/s for the whole job, the HBM roofline of the K-scan
+kernel (HIP events around every launch, taken live in a second timed pass of
+the same steps), the host-link figures of the V pull, and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import kcache_inputs as ki  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload of BASELINE.json (1-5)")
+    ap.add_argument("--layers", type=int, default=0, help="debug: use fewer layers (invalid as a result)")
+    ap.add_argument("--parts", type=int, default=0, help="pipeline parts per layer (0 = library default)")
+    ap.add_argument("--gather", choices=["zerocopy", "staged"], default="zerocopy")
+    ap.add_argument("--cpu-units", type=int, default=64, help="units in the CPU-oracle sample")
+    ap.add_argument("--cpu-passes", type=int, default=3, help="oracle passes over the sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probes", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the method's units are independent; "
+              "see DESIGN.md for how it would shard); --gpus %d is not supported" % a.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    import paper_2404_18057_amd as kc
+
+    wl = ki.config(a.config)
+    L = a.layers if a.layers > 0 else wl.L
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    ctx = kc.Context(0, kc.workspace_bytes(wl.B, wl.H, wl.S_cap, wl.N))
+    ctx.set_pipeline_parts(a.parts)
+    mode = kc.GATHER_ZEROCOPY if a.gather == "zerocopy" else kc.GATHER_STAGED
+    dt = ki.torch_dtype(wl.dtype)
+    lens = wl.seq_lens()
+    lens_dev = torch.from_numpy(lens).to(dev)
+    pos_last = torch.from_numpy(lens - 1).to(dev)
+
+    # ---- resident state: K in HBM, V in pinned host memory, placed by the store path
+    t0 = time.time()
+    caches, qs, k_tok, v_tok = [], [], [], []
+    shape = (wl.B, wl.Hkv, wl.S_cap, wl.d)
+    T_chunk = min(wl.S_cap, 8192)
+    hks = list(range(wl.Hkv))
+    for layer in range(L):
+        k_cache = torch.empty(shape, dtype=dt, device=dev)
+        v_cache = torch.empty(shape, dtype=dt, pin_memory=True)
+        cache = kc.LayerCache(k_cache, v_cache)
+        kt = torch.empty((wl.B, 1, wl.Hkv, wl.d), dtype=dt, device=dev)
+        vt = torch.empty((wl.B, 1, wl.Hkv, wl.d), dtype=dt, device=dev)
+        for b in range(wl.B):
+            k, v = ki.gen_kv_units(wl, layer, b, hks, wl.S_cap, dev)
+            sub = kc.LayerCache(k_cache[b:b + 1], v_cache[b:b + 1])
+            zero = torch.zeros(1, dtype=torch.int32, device=dev)
+            for t in range(0, wl.S_cap, T_chunk):
+                kn = k[:, t:t + T_chunk].permute(1, 0, 2).unsqueeze(0).contiguous()
+                vn = v[:, t:t + T_chunk].permute(1, 0, 2).unsqueeze(0).contiguous()
+                ctx.prefill_store(sub, kn, vn, zero + t)
+            kt[b, 0] = k[:, lens[b] - 1]
+            vt[b, 0] = v[:, lens[b] - 1]
+            ctx.synchronize()
+            torch.cuda.synchronize()
+        caches.append(cache)
+        qs.append(ki.gen_q(wl, layer, dev))
+        k_tok.append(kt)
+        v_tok.append(vt)
+    ctx.device_check()
+    setup_s = time.time() - t0
+
+    outs = [torch.empty((wl.B, wl.H, wl.d), dtype=torch.float32, device=dev) for _ in range(L)]
+    idxs = [torch.empty((wl.B, wl.H, wl.N), dtype=torch.int32, device=dev) for _ in range(L)]
+    ws = [torch.empty((wl.B, wl.H, wl.N), dtype=torch.float32, device=dev) for _ in range(L)]
+
+    def step():
+        for l in range(L):
+            ctx.prefill_store(caches[l], k_tok[l], v_tok[l], pos_last)
+            ctx.decode_attention(caches[l], qs[l], lens_dev, wl.N, out=outs[l], idx_out=idxs[l],
+                                 w_out=ws[l], gather_mode=mode)
+
+    def timed(n):
+        torch.cuda.synchronize()
+        ctx.synchronize()
+        t = time.perf_counter()
+        for _ in range(n):
+            step()
+        ctx.synchronize()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / n
+
+    for _ in range(a.warmup):
+        step()
+    sec_per_step = timed(a.steps)
+
+    # ---- second pass of the same steps with HIP events around every kernel launch
+    ctx.set_profile(True)
+    ctx.profile_reset()
+    sec_per_step_prof = timed(a.steps)
+    prof = {k: ctx.profile_read(k) for k in kc.KERNELS}
+    ctx.set_profile(False)
+    ctx.device_check()
+
+    units_per_layer = wl.B * wl.H
+    k_bytes_layer = int(lens.astype(np.int64).sum()) * wl.Hkv * wl.d * 2
+    n_eff = np.minimum(lens, wl.N).astype(np.int64)
+    v_bytes_layer = int(n_eff.sum()) * wl.H * wl.d * 2
+    scan_ms, scan_n = prof["kscan"]
+    gat_ms, gat_n = prof["gather"]
+    sel_ms, sel_n = prof["select"]
+    scan_gbps = k_bytes_layer * L * a.steps / (scan_ms * 1e-3) / 1e9 if scan_ms else 0.0
+    gather_gbps = v_bytes_layer * L * a.steps / (gat_ms * 1e-3) / 1e9 if gat_ms else 0.0
+
+    # ---- measured denominators
+    probes = {}
+    if not a.no_probes:
+        kflat = caches[0].k.view(-1)
+        vflat = caches[0].v.view(-1)
+        n1g = min(vflat.numel(), (1 << 30) // 2)
+        probes["hbm_stream_read_GBps"] = ctx.probe_read(kflat, iters=5)
+        stage = torch.empty(n1g, dtype=dt, device=dev)
+        pinned = torch.empty(n1g, dtype=dt, pin_memory=True)
+        probes["h2d_pinned_copy_GBps"] = ctx.probe_copy(stage, vflat[:n1g], iters=5)
+        probes["d2h_pinned_copy_GBps"] = ctx.probe_copy(pinned, stage, iters=5)
+        probes["zerocopy_stream_read_GBps"] = ctx.probe_read(vflat[:n1g], iters=3)
+        probes["zerocopy_row_read_GBps"] = ctx.probe_rows(vflat, 1 << 20, iters=3)
+        del stage, pinned
+
+    result = {
+        "metric": "KCache decode-attn tokens/s",
+        "value": wl.B / sec_per_step,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": sec_per_step * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": wl.name, "layers": L, "batch": wl.B, "q_heads": wl.H,
+                   "kv_heads": wl.Hkv, "head_dim": wl.d, "context": int(lens.max()), "top_n": wl.N,
+                   "gather": a.gather, "pipeline_parts": a.parts,
+                   "k_cache_GiB": L * np.prod(shape) * 2 / 2 ** 30, "setup_s": round(setup_s, 1)},
+        "roofline": {
+            "bound": "hbm", "kernel": "kscan_kernel",
+            "achieved": scan_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": scan_gbps / HBM_PEAK_GBPS,
+            "traffic": None,
+            "bytes_per_launch": k_bytes_layer * L * a.steps / max(scan_n, 1),
+            "avg_launch_ms": scan_ms / max(scan_n, 1), "launches": scan_n,
+        },
+        "v_gather": {
+            "achieved": gather_gbps, "unit": "GB/s", "bytes_per_step": v_bytes_layer * L,
+            "avg_launch_ms": gat_ms / max(gat_n, 1), "launches": gat_n,
+            "peak_measured_h2d": probes.get("h2d_pinned_copy_GBps"),
+            "frac_of_measured": (gather_gbps / probes["h2d_pinned_copy_GBps"]
+                                 if probes.get("h2d_pinned_copy_GBps") else None),
+            "link_busy_frac_of_step": (v_bytes_layer * L / sec_per_step / 1e9 /
+                                       probes["h2d_pinned_copy_GBps"]
+                                       if probes.get("h2d_pinned_copy_GBps") else None),
+        },
+        "select": {"avg_launch_ms": sel_ms / max(sel_n, 1), "launches": sel_n},
+        "ms_per_step_with_event_profiling": sec_per_step_prof * 1e3,
+        "k_scan_GBps_of_step": k_bytes_layer * L / sec_per_step / 1e9,
+        "probes": probes,
+    }
+
+    if not a.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, L, a.cpu_units, a.cpu_passes, outs, idxs, ws)
+    print(json.dumps(result))
+
+
+def cpu_baseline(wl, L, n_units, passes, outs, idxs, ws):
+    """The CPU oracle, as it stands, on a seeded sample of this workload's units,
+    one thread per available core; its results double as a spot check of the GPU
+    outputs of the last timed step."""
+    import oracle
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from harness import check_unit, dtype_code   # the acceptance rule of the parity tests
+    cores = len(os.sched_getaffinity(0))
+    rng = np.random.default_rng(wl.seed)
+    lens = wl.seq_lens()
+    picks = []
+    while len(picks) < n_units:
+        l, b, h = int(rng.integers(L)), int(rng.integers(wl.B)), int(rng.integers(wl.H))
+        if (l, b, h) not in picks:
+            picks.append((l, b, h))
+    s_max = int(max(lens[b] for _, b, _ in picks))
+    q = np.zeros((n_units, 1, wl.d), np.uint16)
+    K = np.zeros((n_units, 1, s_max, wl.d), np.uint16)
+    V = np.zeros((n_units, 1, s_max, wl.d), np.uint16)
+    sl = np.zeros(n_units, np.int32)
+    for i, (l, b, h) in enumerate(picks):
+        qb, kb, vb = ki.gen_unit(wl, l, b, h)
+        q[i, 0], sl[i] = qb, kb.shape[0]
+        K[i, 0, :sl[i]], V[i, 0, :sl[i]] = kb, vb
+    code = dtype_code(wl)
+    t = time.perf_counter()
+    for _ in range(passes):
+        oracle.decode_attention(q, K, V, code, sl, wl.N, nthreads=cores)
+    wall = time.perf_counter() - t
+    units_per_step = L * wl.B * wl.H
+    step_s = wall / (n_units * passes) * units_per_step
+    # spot check of the GPU results against the oracle's, same acceptance rule as the tests
+    checked = identical = 0
+    failures = []
+    for i, (l, b, h) in enumerate(picks[:16]):
+        r = oracle.decode_unit(q[i, 0], K[i, 0, :sl[i]], V[i, 0, :sl[i]], code, wl.N,
+                               want_scores=True)
+        r["v"] = oracle.decode16(V[i, 0, :sl[i]], code)
+        try:
+            identical += check_unit(r, wl.N, outs[l][b, h].cpu().numpy(),
+                                    idxs[l][b, h].cpu().numpy(), ws[l][b, h].cpu().numpy())
+            checked += 1
+        except AssertionError as e:
+            failures.append("%s: %s" % ((l, b, h), e))
+    return {"value": wl.B / step_s, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "%d of %d (layer, sequence, head) units of %s, regenerated on the host, "
+                      "fp64 oracle with %d threads, %d passes, %.2f s wall (%.1f core-seconds); scaled to "
+                      "a full step" % (n_units, units_per_step, wl.name, cores, passes, wall,
+                                       wall * cores),
+            "extrapolated": True,
+            "gpu_spot_check": {"units": checked, "index_sets_identical": identical,
+                               "failures": failures}}
+
+
+if __name__ == "__main__":
+    main()

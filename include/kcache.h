@@ -75,7 +75,8 @@ typedef enum {
   KC_KERNEL_GATHER = 2,  /* V row pull + weighted sum (host-link bound)              */
   KC_KERNEL_STORE_K = 3, /* cache store, K half                                      */
   KC_KERNEL_STORE_V = 4, /* cache store, V half (device to host)                     */
-  KC_KERNEL_COUNT = 5
+  KC_KERNEL_FUSED = 5,   /* scan + select + V pull + weighted sum in one launch      */
+  KC_KERNEL_COUNT = 6
 } kc_kernel_id;
 
 /* Integer options for kcache_set_option. */
@@ -85,7 +86,10 @@ typedef enum {
                                 scan of the next; 0 = choose automatically            */
   KC_OPT_PROFILE = 1,        /* 1: bracket every kernel with HIP events (see
                                 kcache_profile_read); 0: off (default)                */
-  KC_OPT_STAGED_THREADS = 2  /* host threads packing rows in KC_GATHER_STAGED mode    */
+  KC_OPT_STAGED_THREADS = 2, /* host threads packing rows in KC_GATHER_STAGED mode    */
+  KC_OPT_FUSED = 3           /* 1 (default): KC_GATHER_ZEROCOPY decodes run as one fused
+                                launch per layer whose scores never leave the chip;
+                                0: separate scan / select / gather launches            */
 } kc_option;
 
 /* Create a context on `device` (a HIP device ordinal) with a workspace of at

@@ -110,7 +110,9 @@ struct kc_ctx {
   size_t ws_bytes = 0;
   int* flags = nullptr;  // [0] device-check bits, [16] probe sink
   std::string err;
-  int parts = 0, profile = 0, staged_threads = 8;
+  int parts = 0, profile = 0, staged_threads = 8, fused = 1;
+  int* counters = nullptr;  // per KV unit arrival tickets of the fused kernel, zero when idle
+  size_t counters_n = 0;
   std::vector<ProfRec> pending;
   std::vector<hipEvent_t> free_events;
   double prof_ms[KC_KERNEL_COUNT] = {};
@@ -224,6 +226,32 @@ int ensure_workspace(kc_ctx* c, size_t bytes) {
   return KC_OK;
 }
 
+int ensure_counters(kc_ctx* c, size_t n) {
+  if (n <= c->counters_n) return KC_OK;
+  KC_HIP(c, hipDeviceSynchronize());
+  if (c->counters) (void)hipFree(c->counters);
+  c->counters = nullptr;
+  c->counters_n = 0;
+  hipError_t e = hipMalloc((void**)&c->counters, n * sizeof(int));
+  if (e != hipSuccess)
+    return fail(c, KC_ERR_WORKSPACE, "ticket counters for %zu units: %s", n, hipGetErrorString(e));
+  KC_HIP(c, hipMemset(c->counters, 0, n * sizeof(int)));
+  c->counters_n = n;
+  return KC_OK;
+}
+
+// Workspace of the unfused path: fp32 scores [units][S_cap], positions and weights [units][N].
+size_t unfused_bytes(size_t units, size_t S_cap, size_t N) {
+  return round256(units * S_cap * sizeof(float)) + 2 * round256(units * N * sizeof(int32_t));
+}
+
+// Workspace of the fused path: chunk-local candidates (score + position), chunk
+// partials, positions and weights.
+size_t fused_bytes(size_t units, size_t chunks_cap, size_t kk, size_t N) {
+  return 2 * round256(units * chunks_cap * kk * sizeof(float)) +
+         round256(units * chunks_cap * sizeof(float2)) + 2 * round256(units * N * sizeof(int32_t));
+}
+
 int ensure_staged(kc_ctx* c, size_t rows) {
   if (!c->pool || c->pool->size() != std::max(0, c->staged_threads - 1)) {
     delete c->pool;
@@ -304,7 +332,10 @@ const char* kcache_version(void) { return "kcache-gfx950 0.1"; }
 size_t kcache_workspace_bytes(int32_t B, int32_t H, int32_t S_cap, int32_t N) {
   if (!sizes_ok(B, H, S_cap, N)) return 0;
   const size_t units = (size_t)B * H;
-  return round256(units * S_cap * sizeof(float)) + 2 * round256(units * N * sizeof(int32_t));
+  // the fused path never keeps more than min(N, R) candidates per R >= 512 positions
+  const size_t chunks = ((size_t)S_cap + kc::kFusedThreads - 1) / kc::kFusedThreads;
+  const size_t kk = std::min<size_t>(N, kc::kFusedThreads);
+  return std::max(unfused_bytes(units, S_cap, N), fused_bytes(units, chunks, kk, N));
 }
 
 int kcache_check_shapes(const kc_layer_cache* cache, int32_t H, int32_t N) {
@@ -376,6 +407,7 @@ int kcache_destroy(kc_ctx* c) {
   if (c->store_side) (void)hipStreamDestroy(c->store_side);
   if (c->ws) (void)hipFree(c->ws);
   if (c->flags) (void)hipFree(c->flags);
+  if (c->counters) (void)hipFree(c->counters);
   if (c->h_idx) (void)hipHostFree(c->h_idx);
   if (c->h_rows) (void)hipHostFree(c->h_rows);
   if (c->d_rows) (void)hipFree(c->d_rows);
@@ -395,6 +427,9 @@ int kcache_set_option(kc_ctx* c, int32_t option, int64_t value) {
       return KC_OK;
     case KC_OPT_PROFILE:
       c->profile = value != 0;
+      return KC_OK;
+    case KC_OPT_FUSED:
+      c->fused = value != 0;
       return KC_OK;
     case KC_OPT_STAGED_THREADS:
       if (value < 1 || value > 256)
@@ -425,16 +460,25 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
 
   hipStream_t st = (hipStream_t)stream;
   const kc::Shape sh{cache->B, 0, cache->Hkv, cache->S_cap, 0, cache->dtype};
-  // V first: the side stream starts as soon as the inputs are ready on `st`
-  KC_HIP(c, hipEventRecord(c->ev_fork, st));
-  KC_HIP(c, hipStreamWaitEvent(c->store_side, c->ev_fork, 0));
-  {
-    KernelTimer t(c, KC_KERNEL_STORE_V, c->store_side);
-    KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, pos_dev, T, c->flags, c->store_side));
+  if ((int64_t)cache->B * T * cache->Hkv <= 4096) {
+    // a decode-step append: too small to be worth a second stream and two event waits
+    {
+      KernelTimer t(c, KC_KERNEL_STORE_V, st);
+      KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, pos_dev, T, c->flags, st));
+    }
+    if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, st));
+  } else {
+    // V first: the side stream starts as soon as the inputs are ready on `st`
+    KC_HIP(c, hipEventRecord(c->ev_fork, st));
+    KC_HIP(c, hipStreamWaitEvent(c->store_side, c->ev_fork, 0));
+    {
+      KernelTimer t(c, KC_KERNEL_STORE_V, c->store_side);
+      KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, pos_dev, T, c->flags, c->store_side));
+    }
+    KC_HIP(c, hipEventRecord(c->ev_store, c->store_side));
+    c->store_pending = true;
+    if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, c->store_side));
   }
-  KC_HIP(c, hipEventRecord(c->ev_store, c->store_side));
-  c->store_pending = true;
-  if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, c->store_side));
   {
     KernelTimer t(c, KC_KERNEL_STORE_K, st);
     KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, pos_dev, T, c->flags, st));
@@ -462,20 +506,18 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
 
   const int B = cache->B, Hkv = cache->Hkv, S_cap = cache->S_cap, G = H / Hkv;
   const size_t units = (size_t)B * H;
-  if ((rc = ensure_workspace(c, kcache_workspace_bytes(B, H, S_cap, N))) != KC_OK) return rc;
+  const int kv_units = B * Hkv;
   const bool staged = gather_mode == KC_GATHER_STAGED;
+  const bool fused = !staged && c->fused;
+  const int R = kc::fused_rows_per_block(kv_units, G, S_cap);
+  const int chunks_cap = (S_cap + R - 1) / R, kk = std::min(N, R);
+  const size_t need = fused ? fused_bytes(units, chunks_cap, kk, N) : unfused_bytes(units, S_cap, N);
+  if ((rc = ensure_workspace(c, need)) != KC_OK) return rc;
   if (staged && (rc = ensure_staged(c, units * N)) != KC_OK) return rc;
-
-  char* wsp = static_cast<char*>(c->ws);
-  float* z = reinterpret_cast<float*>(wsp);
-  wsp += round256(units * S_cap * sizeof(float));
-  int32_t* idx = idx_out_dev ? idx_out_dev : reinterpret_cast<int32_t*>(wsp);
-  wsp += round256(units * N * sizeof(int32_t));
-  float* w = w_out_dev ? w_out_dev : reinterpret_cast<float*>(wsp);
+  if (fused && (rc = ensure_counters(c, kv_units)) != KC_OK) return rc;
 
   hipStream_t st = (hipStream_t)stream;
   const kc::Shape sh{B, H, Hkv, S_cap, N, cache->dtype};
-  const int kv_units = B * Hkv;
   const int parts = pick_parts(c, kv_units, (size_t)kv_units * S_cap * kc::kRowBytes);
 
   // the workspace and the V rows must be free of earlier work of this context
@@ -484,6 +526,50 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
     KC_HIP(c, hipStreamWaitEvent(st, c->ev_store, 0));
     c->store_pending = false;
   }
+
+  if (fused) {
+    char* p = static_cast<char*>(c->ws);
+    kc::FusedArgs a;
+    a.q = static_cast<const uint16_t*>(q_dev);
+    a.K = static_cast<const uint16_t*>(cache->k_dev);
+    a.V = static_cast<const uint16_t*>(v_map);
+    a.seq_lens = seq_lens_dev;
+    a.out = out_dev;
+    a.cand_z = reinterpret_cast<float*>(p);
+    p += round256(units * chunks_cap * kk * sizeof(float));
+    a.cand_pos = reinterpret_cast<int32_t*>(p);
+    p += round256(units * chunks_cap * kk * sizeof(float));
+    a.part = reinterpret_cast<float2*>(p);
+    p += round256(units * chunks_cap * sizeof(float2));
+    a.idx = idx_out_dev ? idx_out_dev : reinterpret_cast<int32_t*>(p);
+    p += round256(units * N * sizeof(int32_t));
+    a.w = w_out_dev ? w_out_dev : reinterpret_cast<float*>(p);
+    a.counters = c->counters;
+    a.flags = c->flags;
+    a.H = H;
+    a.Hkv = Hkv;
+    a.S_cap = S_cap;
+    a.N = N;
+    a.R = R;
+    a.chunks_cap = chunks_cap;
+    a.kk = kk;
+    a.kv0 = 0;
+    a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
+    {
+      KernelTimer t(c, KC_KERNEL_FUSED, st);
+      KC_HIP(c, kc::launch_fused(a, cache->dtype, kv_units, st));
+    }
+    KC_HIP(c, hipEventRecord(c->ev_last, st));
+    c->have_last = true;
+    return KC_OK;
+  }
+
+  char* wsp = static_cast<char*>(c->ws);
+  float* z = reinterpret_cast<float*>(wsp);
+  wsp += round256(units * S_cap * sizeof(float));
+  int32_t* idx = idx_out_dev ? idx_out_dev : reinterpret_cast<int32_t*>(wsp);
+  wsp += round256(units * N * sizeof(int32_t));
+  float* w = w_out_dev ? w_out_dev : reinterpret_cast<float*>(wsp);
 
   auto part_range = [&](int p, int* kv0, int* cnt) {
     *kv0 = (int)((int64_t)kv_units * p / parts);

@@ -1,0 +1,333 @@
+// Fused KCache decode attention: one launch per layer does the K scan, the
+// softmax statistics, the top-N selection, the V pull and the weighted sum
+// (paper section 3.1 and Table 1 rows S~ and A~; Figure 1 lower half).
+//
+// Why one kernel.  The K scan is a pure HBM read stream (arithmetic intensity
+// about 1, Table 1) and the V pull is bound by the host link (section 3.2,
+// equation (3)); they only overlap if some (sequence, head) units are already
+// pulling V rows while others are still being scanned.  Writing all fp32
+// scores back to HBM for a separate selection kernel costs the read stream
+// about 15 % (measured: interleaved small writes), so the scores never leave
+// the chip:
+//
+//   1. a workgroup scores R consecutive positions of one (sequence, KV head)
+//      for all G query heads of the group and keeps the scores in LDS;
+//   2. it reduces them to what the rest of the method needs: the chunk's
+//      softmax partials (max, sum of exp) and its own top-min(N, R) scores
+//      with their positions -- any member of the unit's global top-N is
+//      necessarily in the top-N of its chunk under the same ordering, so the
+//      union of the chunk lists is an exact candidate set;
+//   3. the workgroup that finishes a unit last (ticket counter) merges the
+//      chunk lists: combines the partials into the full-context softmax
+//      normaliser, selects the final top-N among the candidates, writes
+//      positions and weights, pulls the N rows of V from mapped host memory
+//      and accumulates the output.  No workgroup ever waits for another.
+//
+// Units finish at different times (chunks of one unit are adjacent in the
+// grid), so the V pulls of early units overlap the K scan of later ones.
+#include "kc_internal.h"
+#include "topn.cuh"
+
+namespace kc {
+namespace {
+
+constexpr int FT = kFusedThreads;
+constexpr int FW = FT / 64;
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf162_t __attribute__((ext_vector_type(2)));
+
+template <int DT>
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
+  if constexpr (DT == 0) {
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b),
+                                  acc, false);
+  } else {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf162_t, a),
+                                           __builtin_bit_cast(bf162_t, b), acc, false);
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ float dot8(const uint4& k, const uint4& q) {
+  float a = dot2<DT>(k.x, q.x, 0.f);
+  a = dot2<DT>(k.y, q.y, a);
+  a = dot2<DT>(k.z, q.z, a);
+  return dot2<DT>(k.w, q.w, a);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true);
+  return x + __builtin_bit_cast(float, y);
+}
+
+__device__ __forceinline__ float row16_sum(float x) {
+  x = dpp_add<0xB1>(x);   // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);   // quad_perm [2,3,0,1]
+  x = dpp_add<0x141>(x);  // row_half_mirror
+  x = dpp_add<0x140>(x);  // row_mirror
+  return x;
+}
+
+template <int DT>
+__device__ __forceinline__ void fma8(float (&acc)[8], const uint4& v, float w) {
+  const uint32_t r[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float lo, hi;
+    if constexpr (DT == 0) {
+      half2_t h = __builtin_bit_cast(half2_t, r[i]);
+      lo = (float)h.x;
+      hi = (float)h.y;
+    } else {
+      lo = __uint_as_float(r[i] << 16);
+      hi = __uint_as_float(r[i] & 0xffff0000u);
+    }
+    acc[2 * i] = fmaf(w, lo, acc[2 * i]);
+    acc[2 * i + 1] = fmaf(w, hi, acc[2 * i + 1]);
+  }
+}
+
+struct Smem {
+  float z[kFusedZFloats];  // scores of this chunk, [G][R]; reused for the merge
+  TopNScratch<FT> sc;
+  int last;
+};
+
+// V pull + weighted sum for one unit by the whole workgroup: 32 row slots of 16
+// lanes, 8 independent 256-byte reads per slot in flight.
+template <int DT>
+__device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp,
+                                                    const int32_t* __restrict__ iu,
+                                                    const float* __restrict__ wu, int n_eff,
+                                                    float* __restrict__ out_u, Smem* sm) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane & 15, rg = lane >> 4;
+  const int slot = wave * 4 + rg;
+  constexpr int SLOTS = FW * 4, UNR = 8;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int j0 = slot; j0 < n_eff; j0 += SLOTS * UNR) {
+    int t[UNR];
+    float w[UNR];
+    uint4 v[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int j = j0 + u * SLOTS;
+      t[u] = (j < n_eff) ? iu[j] : -1;
+      w[u] = (j < n_eff) ? wu[j] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      v[u] = make_uint4(0, 0, 0, 0);
+      if (t[u] >= 0) v[u] = Vp[(size_t)t[u] * 16 + sub];
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      if (t[u] >= 0) fma8<DT>(acc, v[u], w[u]);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    acc[i] += __shfl_xor(acc[i], 16, 64);
+    acc[i] += __shfl_xor(acc[i], 32, 64);
+  }
+  float* part = reinterpret_cast<float*>(sm->sc.hist);  // [FW][128] floats = 4 KiB
+  __syncthreads();
+  if (rg == 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) part[wave * kHeadDim + sub * 8 + i] = acc[i];
+  }
+  __syncthreads();
+  if (threadIdx.x < kHeadDim) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < FW; ++w) t += part[w * kHeadDim + threadIdx.x];
+    out_u[threadIdx.x] = t;
+  }
+  __syncthreads();
+}
+
+template <int DT, int G>
+__global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
+  __shared__ Smem sm;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = lane & 15, rg = lane >> 4;
+  const int chunk = blockIdx.x % a.chunks_cap;
+  const int ku = a.kv0 + blockIdx.x / a.chunks_cap;
+  const int b = ku / a.Hkv, hk = ku - b * a.Hkv;
+  const int R = a.R, N = a.N, kk = a.kk;
+  int s = a.seq_lens[b];
+  if (s < 1 || s > a.S_cap) {
+    if (tid == 0 && chunk == 0) atomicOr(a.flags, kFlagBadSeqLen);
+    s = s < 1 ? 0 : a.S_cap;
+  }
+  const int unit0 = b * a.H + hk * G;  // first query head of the group
+  if (s == 0) {                        // nothing cached: defined output, no work
+    if (chunk == 0) {
+      for (int g = 0; g < G; ++g) {
+        for (int j = tid; j < N; j += FT) {
+          a.idx[(size_t)(unit0 + g) * N + j] = -1;
+          a.w[(size_t)(unit0 + g) * N + j] = 0.f;
+        }
+        if (tid < kHeadDim) a.out[(size_t)(unit0 + g) * kHeadDim + tid] = 0.f;
+      }
+    }
+    return;
+  }
+  const int row0 = chunk * R;
+  if (row0 >= s) return;
+  const int chunks_b = (s + R - 1) / R;
+  const int n = (s - row0 < R) ? s - row0 : R;  // valid rows of this chunk
+
+  // ---------------- 1. scores of R positions for the G heads of the group -> LDS
+  {
+    uint4 qv[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      qv[g] = *reinterpret_cast<const uint4*>(a.q + (size_t)(unit0 + g) * kHeadDim + sub * 8);
+    const uint4* __restrict__ Kp =
+        reinterpret_cast<const uint4*>(a.K + (size_t)ku * a.S_cap * kHeadDim);
+    const int rows_per_wave = R / FW;  // a multiple of 64
+#pragma unroll 1
+    for (int it = 0; it < rows_per_wave / 64; ++it) {
+      const int local = wave * rows_per_wave + it * 64;
+      const int base = row0 + local;
+      if (base >= s) break;
+      uint4 kr[16];
+      if (base + 64 <= a.S_cap) {
+        const uint4* p = Kp + (size_t)(base + rg) * 16 + sub;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) kr[u] = load_stream16(p + u * 64);
+      } else {  // last rows of the cache: never read beyond S_cap
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          int r = base + u * 4 + rg;
+          r = r < a.S_cap ? r : a.S_cap - 1;
+          kr[u] = Kp[(size_t)r * 16 + sub];
+        }
+      }
+      float keep[G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) keep[g] = 0.f;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const float x = row16_sum(dot8<DT>(kr[u], qv[g]));
+          keep[g] = (sub == u) ? x : keep[g];
+        }
+      }
+#pragma unroll
+      for (int g = 0; g < G; ++g) sm.z[g * R + local + sub * 4 + rg] = keep[g] * a.scale;
+    }
+  }
+  __syncthreads();
+
+  // ---------------- 2. per head: softmax partials and the chunk's own top-min(N, R)
+  const int k_loc = kk < n ? kk : n;
+#pragma unroll 1
+  for (int g = 0; g < G; ++g) {
+    const float* keys = sm.z + g * R;
+    const size_t slot = (size_t)(unit0 + g) * a.chunks_cap + chunk;
+    float m = -INFINITY;
+    for (int i = tid; i < n; i += FT) m = fmaxf(m, keys[i]);
+    m = block_max<FT>(m, &sm.sc);
+    float l = 0.f;
+    for (int i = tid; i < n; i += FT) l += __expf(keys[i] - m);
+    l = block_sum<FT>(l, &sm.sc);
+    if (tid == 0) a.part[slot] = make_float2(m, l);
+    float* cz = a.cand_z + slot * kk;
+    int32_t* cp = a.cand_pos + slot * kk;
+    block_topn<FT>(keys, n, k_loc, &sm.sc, [&](int r, int i, float v) {
+      cz[r] = v;
+      cp[r] = row0 + i;
+    });
+  }
+
+  // ---------------- 3. the workgroup that completes the unit merges and pulls V
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const int ticket = atomicAdd(a.counters + ku, 1);
+    sm.last = (ticket == chunks_b - 1);
+  }
+  __syncthreads();
+  if (!sm.last) return;
+  __threadfence();
+  if (tid == 0) a.counters[ku] = 0;  // ready for the next launch
+
+  const int n_eff = N < s ? N : s;
+  const int last_rows = s - (chunks_b - 1) * R;
+  const int M = (chunks_b - 1) * kk + (kk < last_rows ? kk : last_rows);  // candidates
+  const uint4* __restrict__ Vp =
+      reinterpret_cast<const uint4*>(a.V) + (size_t)ku * a.S_cap * 16;
+#pragma unroll 1
+  for (int g = 0; g < G; ++g) {
+    const int unit = unit0 + g;
+    const size_t slot0 = (size_t)unit * a.chunks_cap;
+    // full-context softmax normaliser from the chunk partials
+    float m = -INFINITY;
+    for (int c = tid; c < chunks_b; c += FT) m = fmaxf(m, a.part[slot0 + c].x);
+    m = block_max<FT>(m, &sm.sc);
+    float Z = 0.f;
+    for (int c = tid; c < chunks_b; c += FT) {
+      const float2 p = a.part[slot0 + c];
+      Z += p.y * __expf(p.x - m);
+    }
+    Z = block_sum<FT>(Z, &sm.sc);
+    const float inv_Z = 1.f / Z;
+    // the unit's candidates are contiguous: every chunk but the last holds kk
+    const float* cz = a.cand_z + slot0 * kk;
+    const int32_t* cp = a.cand_pos + slot0 * kk;
+    const float* keys = cz;
+    if (M <= kFusedZFloats) {
+      for (int i = tid; i < M; i += FT) sm.z[i] = cz[i];
+      __syncthreads();
+      keys = sm.z;
+    }
+    int32_t* iu = a.idx + (size_t)unit * N;
+    float* wu = a.w + (size_t)unit * N;
+    block_topn<FT>(keys, M, n_eff, &sm.sc, [&](int r, int i, float v) {
+      iu[r] = cp[i];
+      wu[r] = expf(v - m) * inv_Z;
+    });
+    for (int j = n_eff + tid; j < N; j += FT) {
+      iu[j] = -1;
+      wu[j] = 0.f;
+    }
+    __syncthreads();  // positions and weights are visible to the whole workgroup
+    pull_and_accumulate<DT>(Vp, iu, wu, n_eff, a.out + (size_t)unit * kHeadDim, &sm);
+  }
+}
+
+template <int DT>
+hipError_t launch_dt(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
+  const dim3 grid((unsigned)(kv_count * a.chunks_cap)), block(FT);
+  switch (G) {
+    case 1: hipLaunchKernelGGL((fused_kernel<DT, 1>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((fused_kernel<DT, 2>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((fused_kernel<DT, 4>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((fused_kernel<DT, 8>), grid, block, 0, st, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+int fused_rows_per_block(int kv_units, int G, int S_cap) {
+  int R = kFusedZFloats / G;
+  while (R > kFusedThreads && (int64_t)kv_units * ((S_cap + R - 1) / R) < 2048) R /= 2;
+  return R;
+}
+
+hipError_t launch_fused(const FusedArgs& a, int dtype, int kv_count, hipStream_t st) {
+  if (kv_count <= 0) return hipSuccess;
+  const int G = a.H / a.Hkv;
+  if (a.R % kFusedThreads != 0 || a.R * G > kFusedZFloats) return hipErrorInvalidValue;
+  return dtype == 0 ? launch_dt<0>(a, G, kv_count, st) : launch_dt<1>(a, G, kv_count, st);
+}
+
+}  // namespace kc

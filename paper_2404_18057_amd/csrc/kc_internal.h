@@ -11,6 +11,8 @@ constexpr int kHeadDim = 128;           // d_h: one row = 128 16-bit values = 25
 constexpr int kRowBytes = 256;
 constexpr int kScanRowsPerBlock = 1024;  // K rows scored by one workgroup
 constexpr int kSelectThreads = 512;
+constexpr int kFusedThreads = 512;       // workgroup size of the fused decode kernel
+constexpr int kFusedZFloats = 8192;      // fp32 scores one workgroup keeps in LDS ([G][R])
 
 // 16-byte load that tells the caches the data will not be used again.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -48,6 +50,31 @@ hipError_t launch_gather(const Shape& sh, const void* v, const int32_t* idx, con
 // Copy rows of src [B][T][Hkv][d] to dst [B][Hkv][S_cap][d] at pos[b] + t.
 hipError_t launch_store(const Shape& sh, const void* src, void* dst, const int32_t* pos, int T,
                         int* flags, hipStream_t st);
+
+// Fused decode kernel (decode_fused.hip): scan + local top-N per chunk, merge,
+// V pull and weighted sum in one launch.
+struct FusedArgs {
+  const uint16_t* q;
+  const uint16_t* K;
+  const uint16_t* V;  // device-visible address of the mapped host cache
+  const int32_t* seq_lens;
+  float* out;
+  int32_t* idx;
+  float* w;
+  float* cand_z;      // [units][chunks_cap][kk] chunk-local top scores
+  int32_t* cand_pos;  // their positions
+  float2* part;       // [units][chunks_cap] (max, sum of exp) of each chunk
+  int* counters;      // [kv units] arrival tickets, zero between launches
+  int* flags;
+  int H, Hkv, S_cap, N;
+  int R;           // positions per workgroup, a multiple of kFusedThreads, R * G <= kFusedZFloats
+  int chunks_cap;  // ceil(S_cap / R)
+  int kk;          // min(N, R): candidates kept per chunk
+  int kv0;
+  float scale;
+};
+int fused_rows_per_block(int kv_units, int G, int S_cap);
+hipError_t launch_fused(const FusedArgs& a, int dtype, int kv_count, hipStream_t st);
 
 hipError_t launch_probe_read(const void* ptr, size_t bytes, uint32_t* sink, hipStream_t st);
 hipError_t launch_probe_rows(const void* ptr, size_t total_rows, int64_t n_rows, uint32_t* sink,

@@ -18,9 +18,13 @@ def kc():
     return kc
 
 
-@pytest.fixture(scope="module")
-def ctx(kc):
+@pytest.fixture(scope="module", params=["fused", "unfused"])
+def ctx(kc, request):
+    """Every test runs on both decode paths: the fused single launch (default)
+    and the separate scan / select / gather launches."""
     c = kc.Context(0)
+    c.set_fused(request.param == "fused")
+    c.fused_default = request.param == "fused"
     yield c
     c.close()
 
@@ -75,11 +79,13 @@ def test_config1_every_unit(kc, ctx):
 def test_config1_pipelined_parts_give_identical_results(kc, ctx, parts):
     wl = ki.config(1)
     cache, q, lens, _, _ = build_layer(ctx, wl, 0)
+    ctx.set_fused(False)            # parts only exist on the unfused path
     ctx.set_pipeline_parts(1)
     _, _, base = run_and_check(ctx, wl, 0, cache, q, lens, [(0, 0)])
     ctx.set_pipeline_parts(parts)
     _, _, got = run_and_check(ctx, wl, 0, cache, q, lens, sample_units(wl, 10 ** 9))
     ctx.set_pipeline_parts(0)
+    ctx.set_fused(ctx.fused_default)
     for a, b in zip(base, got):
         assert np.array_equal(a, b)
 
@@ -187,7 +193,9 @@ def test_other_group_sizes(kc, ctx, G):
 def test_staged_gather_matches_zero_copy(kc, ctx):
     wl = ki.config(1)
     cache, q, lens, _, _ = build_layer(ctx, wl, 0)
+    ctx.set_fused(False)            # same kernels on both sides: results must be bit-equal
     _, _, a = run_and_check(ctx, wl, 0, cache, q, lens, sample_units(wl, 10 ** 9))
+    ctx.set_fused(ctx.fused_default)
     for threads in (1, 4):
         ctx.set_staged_threads(threads)
         _, _, b = run_and_check(ctx, wl, 0, cache, q, lens, sample_units(wl, 10 ** 9),
@@ -203,6 +211,30 @@ def test_results_are_deterministic(kc, ctx):
     _, _, b = run_and_check(ctx, wl, 0, cache, q, lens, [(7, 31)])
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
+
+
+def test_fused_and_unfused_paths_agree(kc, ctx):
+    # same index sets wherever neither is in a tie band (checked against the oracle by
+    # the other tests); here: positions identical, weights and outputs to fp32 rounding
+    wl = ki.config(4, B=6, N=200)
+    cache, q, lens, _, _ = build_layer(ctx, wl, 0)
+    res = {}
+    for fused in (True, False):
+        ctx.set_fused(fused)
+        _, _, res[fused] = run_and_check(ctx, wl, 0, cache, q, lens, sample_units(wl, 12))
+    ctx.set_fused(ctx.fused_default)
+    assert np.array_equal(res[True][1], res[False][1])
+    assert np.allclose(res[True][2], res[False][2], rtol=1e-5, atol=1e-9)
+    assert np.allclose(res[True][0], res[False][0], rtol=1e-4, atol=1e-6)
+
+
+def test_fused_counters_are_clean_between_calls_of_different_shapes(kc, ctx):
+    # the ticket counters return to zero after every launch: alternate shapes on one context
+    for cfg, kw in ((1, {}), (4, dict(B=5, N=48)), (1, dict(S_cap=3000, N=700)), (3, dict(B=3, S_cap=1500))):
+        wl = ki.config(cfg, **kw)
+        cache, q, lens, _, _ = build_layer(ctx, wl, 0)
+        for _ in range(2):
+            run_and_check(ctx, wl, 0, cache, q, lens, sample_units(wl, 6))
 
 
 # ------------------------------------------------------------------ cache store
