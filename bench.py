@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="debug: use fewer layers (invalid as a result)")
     ap.add_argument("--parts", type=int, default=0, help="pipeline parts per layer (0 = library default)")
     ap.add_argument("--gather", choices=["zerocopy", "staged"], default="zerocopy")
+    ap.add_argument("--unfused", action="store_true",
+                    help="separate scan / select / gather launches instead of the fused kernel")
     ap.add_argument("--cpu-units", type=int, default=64, help="units in the CPU-oracle sample")
     ap.add_argument("--cpu-passes", type=int, default=3, help="oracle passes over the sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -63,6 +65,7 @@ def main():
     torch.cuda.set_device(dev)
     ctx = kc.Context(0, kc.workspace_bytes(wl.B, wl.H, wl.S_cap, wl.N))
     ctx.set_pipeline_parts(a.parts)
+    ctx.set_fused(not a.unfused)
     mode = kc.GATHER_ZEROCOPY if a.gather == "zerocopy" else kc.GATHER_STAGED
     dt = ki.torch_dtype(wl.dtype)
     lens = wl.seq_lens()
@@ -136,8 +139,9 @@ def main():
     k_bytes_layer = int(lens.astype(np.int64).sum()) * wl.Hkv * wl.d * 2
     n_eff = np.minimum(lens, wl.N).astype(np.int64)
     v_bytes_layer = int(n_eff.sum()) * wl.H * wl.d * 2
-    scan_ms, scan_n = prof["kscan"]
-    gat_ms, gat_n = prof["gather"]
+    fused_path = prof["fused"][1] > 0
+    scan_ms, scan_n = prof["fused"] if fused_path else prof["kscan"]
+    gat_ms, gat_n = prof["fused"] if fused_path else prof["gather"]
     sel_ms, sel_n = prof["select"]
     scan_gbps = k_bytes_layer * L * a.steps / (scan_ms * 1e-3) / 1e9 if scan_ms else 0.0
     gather_gbps = v_bytes_layer * L * a.steps / (gat_ms * 1e-3) / 1e9 if gat_ms else 0.0
@@ -172,10 +176,11 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "layers": L, "batch": wl.B, "q_heads": wl.H,
                    "kv_heads": wl.Hkv, "head_dim": wl.d, "context": int(lens.max()), "top_n": wl.N,
-                   "gather": a.gather, "pipeline_parts": a.parts,
+                   "gather": a.gather, "path": "fused" if fused_path else "unfused",
+                   "pipeline_parts": a.parts,
                    "k_cache_GiB": L * np.prod(shape) * 2 / 2 ** 30, "setup_s": round(setup_s, 1)},
         "roofline": {
-            "bound": "hbm", "kernel": "kscan_kernel",
+            "bound": "hbm", "kernel": "fused_kernel" if fused_path else "kscan_kernel",
             "achieved": scan_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": scan_gbps / HBM_PEAK_GBPS,
             "traffic": None,
@@ -183,6 +188,7 @@ def main():
             "avg_launch_ms": scan_ms / max(scan_n, 1), "launches": scan_n,
         },
         "v_gather": {
+            "kernel": "fused_kernel (whole launch)" if fused_path else "gather_kernel",
             "achieved": gather_gbps, "unit": "GB/s", "bytes_per_step": v_bytes_layer * L,
             "avg_launch_ms": gat_ms / max(gat_n, 1), "launches": gat_n,
             "peak_measured_h2d": probes.get("h2d_pinned_copy_GBps"),

@@ -89,18 +89,35 @@ __device__ __forceinline__ void fma8(float (&acc)[8], const uint4& v, float w) {
   }
 }
 
+// Data that one workgroup hands to another inside the launch (chunk candidates
+// and partials) is written through to memory and read around the per-XCD L2 with
+// device-scope relaxed atomics (sc1 stores / loads).  That keeps the hand-over
+// coherent across XCDs without the L2 write-back / invalidate walk that a
+// release / acquire fence costs (about 1 us each, thousands per launch).
+template <typename T>
+__device__ __forceinline__ void st_dev(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ T ld_dev(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr int kStage = 1024;  // entries of each of the two staging arrays inside hist[]
+
 struct Smem {
   float z[kFusedZFloats];  // scores of this chunk, [G][R]; reused for the merge
   TopNScratch<FT> sc;
+  float red_out[FW * kHeadDim];
   int last;
 };
 
 // V pull + weighted sum for one unit by the whole workgroup: 32 row slots of 16
-// lanes, 8 independent 256-byte reads per slot in flight.
+// lanes, 8 independent 256-byte reads per slot in flight.  iu / wu may point to
+// LDS or to global memory.
 template <int DT>
-__device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp,
-                                                    const int32_t* __restrict__ iu,
-                                                    const float* __restrict__ wu, int n_eff,
+__device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp, const int32_t* iu,
+                                                    const float* wu, int n_eff,
                                                     float* __restrict__ out_u, Smem* sm) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane & 15, rg = lane >> 4;
@@ -133,17 +150,15 @@ __device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp
     acc[i] += __shfl_xor(acc[i], 16, 64);
     acc[i] += __shfl_xor(acc[i], 32, 64);
   }
-  float* part = reinterpret_cast<float*>(sm->sc.hist);  // [FW][128] floats = 4 KiB
-  __syncthreads();
   if (rg == 0) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) part[wave * kHeadDim + sub * 8 + i] = acc[i];
+    for (int i = 0; i < 8; ++i) sm->red_out[wave * kHeadDim + sub * 8 + i] = acc[i];
   }
   __syncthreads();
   if (threadIdx.x < kHeadDim) {
     float t = 0.f;
 #pragma unroll
-    for (int w = 0; w < FW; ++w) t += part[w * kHeadDim + threadIdx.x];
+    for (int w = 0; w < FW; ++w) t += sm->red_out[w * kHeadDim + threadIdx.x];
     out_u[threadIdx.x] = t;
   }
   __syncthreads();
@@ -226,79 +241,111 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
   __syncthreads();
 
   // ---------------- 2. per head: softmax partials and the chunk's own top-min(N, R)
+  float* const stage_f = reinterpret_cast<float*>(sm.sc.hist);
+  int32_t* const stage_i = reinterpret_cast<int32_t*>(sm.sc.hist) + kStage;
   const int k_loc = kk < n ? kk : n;
+  const bool stage_loc = k_loc <= kStage;
 #pragma unroll 1
   for (int g = 0; g < G; ++g) {
-    const float* keys = sm.z + g * R;
+    const float* zg = sm.z + g * R;
+    auto key = [&](int i) { return zg[i]; };
     const size_t slot = (size_t)(unit0 + g) * a.chunks_cap + chunk;
-    float m = -INFINITY;
-    for (int i = tid; i < n; i += FT) m = fmaxf(m, keys[i]);
-    m = block_max<FT>(m, &sm.sc);
-    float l = 0.f;
-    for (int i = tid; i < n; i += FT) l += __expf(keys[i] - m);
-    l = block_sum<FT>(l, &sm.sc);
-    if (tid == 0) a.part[slot] = make_float2(m, l);
+    const float2 ml = block_softmax_stats<FT>(key, n, &sm.sc);
+    if (tid == 0) {
+      st_dev(&a.part[slot].x, ml.x);
+      st_dev(&a.part[slot].y, ml.y);
+    }
     float* cz = a.cand_z + slot * kk;
     int32_t* cp = a.cand_pos + slot * kk;
-    block_topn<FT>(keys, n, k_loc, &sm.sc, [&](int r, int i, float v) {
-      cz[r] = v;
-      cp[r] = row0 + i;
+    block_topn<FT>(key, n, k_loc, &sm.sc, [&](int r, int i, float v) {
+      if (stage_loc) {  // collect in LDS, then write whole lines
+        stage_f[r] = v;
+        stage_i[r] = row0 + i;
+      } else {
+        st_dev(cz + r, v);
+        st_dev(cp + r, row0 + i);
+      }
     });
+    if (stage_loc) {
+      for (int r = tid; r < k_loc; r += FT) {
+        st_dev(cz + r, stage_f[r]);
+        st_dev(cp + r, stage_i[r]);
+      }
+      __syncthreads();  // the staging area is the next head's histogram
+    }
   }
 
   // ---------------- 3. the workgroup that completes the unit merges and pulls V
-  __threadfence();
+  // Hand-over: every thread waits until its own write-through stores have been
+  // acknowledged, the barrier collects the workgroup, then one thread takes the
+  // unit's ticket.  The last arriver's reads (ld_dev) are issued after its ticket
+  // has returned, so they see every other chunk's lists.
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   if (tid == 0) {
-    const int ticket = atomicAdd(a.counters + ku, 1);
-    sm.last = (ticket == chunks_b - 1);
+    const int ticket =
+        __hip_atomic_fetch_add(a.counters + ku, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = (ticket == chunks_b - 1);
+    if (last) st_dev(a.counters + ku, 0);  // ready for the next launch
+    sm.last = last;
   }
   __syncthreads();
   if (!sm.last) return;
-  __threadfence();
-  if (tid == 0) a.counters[ku] = 0;  // ready for the next launch
 
   const int n_eff = N < s ? N : s;
   const int last_rows = s - (chunks_b - 1) * R;
   const int M = (chunks_b - 1) * kk + (kk < last_rows ? kk : last_rows);  // candidates
+  const bool z_in_lds = M <= kFusedZFloats, pos_in_lds = 2 * M <= kFusedZFloats;
+  const bool stage_out = n_eff <= kStage;
   const uint4* __restrict__ Vp =
       reinterpret_cast<const uint4*>(a.V) + (size_t)ku * a.S_cap * 16;
 #pragma unroll 1
   for (int g = 0; g < G; ++g) {
     const int unit = unit0 + g;
     const size_t slot0 = (size_t)unit * a.chunks_cap;
-    // full-context softmax normaliser from the chunk partials
-    float m = -INFINITY;
-    for (int c = tid; c < chunks_b; c += FT) m = fmaxf(m, a.part[slot0 + c].x);
-    m = block_max<FT>(m, &sm.sc);
-    float Z = 0.f;
-    for (int c = tid; c < chunks_b; c += FT) {
-      const float2 p = a.part[slot0 + c];
-      Z += p.y * __expf(p.x - m);
-    }
-    Z = block_sum<FT>(Z, &sm.sc);
-    const float inv_Z = 1.f / Z;
-    // the unit's candidates are contiguous: every chunk but the last holds kk
+    // the unit's candidates are contiguous: every chunk but the last holds kk.
+    // Everything the merge needs is requested in one batch of bypassing loads.
     const float* cz = a.cand_z + slot0 * kk;
     const int32_t* cp = a.cand_pos + slot0 * kk;
-    const float* keys = cz;
-    if (M <= kFusedZFloats) {
-      for (int i = tid; i < M; i += FT) sm.z[i] = cz[i];
-      __syncthreads();
-      keys = sm.z;
+    float m = -INFINITY, l = 0.f;
+    for (int c = tid; c < chunks_b; c += FT) {
+      const float mc = ld_dev(&a.part[slot0 + c].x), lc = ld_dev(&a.part[slot0 + c].y);
+      const float mm = fmaxf(m, mc);
+      l = (m == mm ? l : l * __expf(m - mm)) + (mc == mm ? lc : lc * __expf(mc - mm));
+      m = mm;
     }
+    int32_t* pos_l = reinterpret_cast<int32_t*>(sm.z) + M;
+    if (z_in_lds)
+      for (int i = tid; i < M; i += FT) sm.z[i] = ld_dev(cz + i);
+    if (pos_in_lds)
+      for (int i = tid; i < M; i += FT) pos_l[i] = ld_dev(cp + i);
+    // full-context softmax normaliser from the chunk partials
+    const float2 mZ = block_merge_stats<FT>(m, l, &sm.sc);  // barriers: LDS copies are visible
+    const float mx = mZ.x, inv_Z = 1.f / mZ.y;
+
     int32_t* iu = a.idx + (size_t)unit * N;
     float* wu = a.w + (size_t)unit * N;
-    block_topn<FT>(keys, M, n_eff, &sm.sc, [&](int r, int i, float v) {
-      iu[r] = cp[i];
-      wu[r] = expf(v - m) * inv_Z;
-    });
+    auto emit = [&](int r, int i, float v) {
+      const int32_t t = pos_in_lds ? pos_l[i] : ld_dev(cp + i);
+      const float w = expf(v - mx) * inv_Z;
+      iu[r] = t;
+      wu[r] = w;
+      if (stage_out) {
+        stage_i[r] = t;
+        stage_f[r] = w;
+      }
+    };
+    if (z_in_lds)
+      block_topn<FT>([&](int i) { return sm.z[i]; }, M, n_eff, &sm.sc, emit);
+    else  // more candidates than the LDS buffer holds: read them around the L2 every pass
+      block_topn<FT>([&](int i) { return ld_dev(cz + i); }, M, n_eff, &sm.sc, emit);
     for (int j = n_eff + tid; j < N; j += FT) {
       iu[j] = -1;
       wu[j] = 0.f;
     }
-    __syncthreads();  // positions and weights are visible to the whole workgroup
-    pull_and_accumulate<DT>(Vp, iu, wu, n_eff, a.out + (size_t)unit * kHeadDim, &sm);
+    // block_topn ended with a barrier: positions and weights are visible to everyone
+    pull_and_accumulate<DT>(Vp, stage_out ? stage_i : iu, stage_out ? stage_f : wu, n_eff,
+                            a.out + (size_t)unit * kHeadDim, &sm);
   }
 }
 

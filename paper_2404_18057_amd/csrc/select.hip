@@ -36,13 +36,10 @@ __global__ __launch_bounds__(NT) void select_kernel(const float* __restrict__ z,
   }
   if (n_eff == 0) return;
 
-  float m = -INFINITY;
-  for (int t = tid; t < s; t += NT) m = fmaxf(m, zr[t]);
-  m = block_max<NT>(m, &sc);
-  float l = 0.f;
-  for (int t = tid; t < s; t += NT) l += __expf(zr[t] - m);
-  const float inv_Z = 1.f / block_sum<NT>(l, &sc);
-  block_topn<NT>(zr, s, n_eff, &sc, [&](int r, int t, float v) {
+  auto key = [&](int t) { return zr[t]; };
+  const float2 ml = block_softmax_stats<NT>(key, s, &sc);
+  const float m = ml.x, inv_Z = 1.f / ml.y;
+  block_topn<NT>(key, s, n_eff, &sc, [&](int r, int t, float v) {
     iu[r] = t;
     wu[r] = expf(v - m) * inv_Z;
   });

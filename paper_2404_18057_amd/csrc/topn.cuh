@@ -1,13 +1,24 @@
 // Block-wide exact top-k selection over fp32 scores (paper section 3.1: "TopN
 // selects the N most relevant results").
 //
-// Scores are mapped to unsigned keys whose integer order is the float order.
-// The k-th largest key T is found by an 11 + 11 + 10 bit radix select with LDS
-// histograms; the kept set is {key > T} plus the first (k - #{key > T})
-// entries with key == T in index order, i.e. "largest first, lower index on
-// ties".  Entries are emitted in ascending index order through an ordered
-// (ballot + prefix) compaction, so nothing depends on the arrival order of an
-// atomic.  The routine works on any flat pointer (LDS or global memory).
+// Scores are mapped to unsigned keys whose integer order is the float order and
+// ordered by (key descending, index ascending): "largest first, lower index on
+// ties".  The k-th entry in that order is the threshold (T, T_idx); an entry is
+// kept iff key > T or (key == T and index <= T_idx).
+//
+//   pass 1   LDS histogram of key bits 31..21 -> the bin holding the k-th entry;
+//   resolve  the few entries of that bin are copied to an LDS list and ranked
+//            against each other directly (all pairs, tie-break included), which
+//            names the threshold entry without further passes;
+//   fallback a bin too crowded for the list (many equal or nearly equal scores)
+//            goes through two more radix passes (bits 20..10, 9..0) and an
+//            index-ordered count of the entries equal to T;
+//   emit     kept entries are written in ascending index order by an ordered
+//            (ballot + prefix) compaction: nothing depends on the arrival order
+//            of an atomic.
+//
+// Scores are read through a caller-supplied accessor keys(i), so they can live
+// in LDS, in global memory, or behind a cache-bypassing load.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -15,14 +26,21 @@
 
 namespace kc {
 
+constexpr int kTopNListCap = 512;
+
 template <int NT>
 struct TopNScratch {
   uint32_t hist[2048];
+  uint32_t list_key[kTopNListCap];
+  int list_idx[kTopNListCap];
   int wave_tot[NT / 64];
-  int seg_gt[NT / 64];
-  int seg_eq[NT / 64];
-  float red[NT / 64];
-  int bin, rank;
+  int seg_a[NT / 64];
+  int seg_b[NT / 64];
+  float red_m[NT / 64];
+  float red_l[NT / 64];
+  int bin, rank, list_cnt;
+  uint32_t thr_key;
+  int thr_idx;
 };
 
 __device__ __forceinline__ uint32_t score_key(float f) {
@@ -82,124 +100,181 @@ __device__ __forceinline__ void find_bin(TopNScratch<NT>* sc, int k) {
   __syncthreads();
 }
 
+// Merges one (max, sum of exp(. - max)) pair per thread into the block's pair,
+// returned to every thread.  Two barriers.  A thread without data carries
+// (-inf, 0); its term vanishes instead of becoming NaN.
 template <int NT>
-__device__ __forceinline__ float block_max(float m, TopNScratch<NT>* sc) {
+__device__ __forceinline__ float2 block_merge_stats(float m, float l, TopNScratch<NT>* sc) {
+  const int tid = threadIdx.x;
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+  for (int o = 32; o > 0; o >>= 1) {
+    const float m2 = __shfl_xor(m, o, 64), l2 = __shfl_xor(l, o, 64);
+    const float mm = fmaxf(m, m2);
+    l = (m == mm ? l : l * __expf(m - mm)) + (m2 == mm ? l2 : l2 * __expf(m2 - mm));
+    m = mm;
+  }
   __syncthreads();
-  if ((threadIdx.x & 63) == 0) sc->red[threadIdx.x >> 6] = m;
+  if ((tid & 63) == 0) {
+    sc->red_m[tid >> 6] = m;
+    sc->red_l[tid >> 6] = l;
+  }
   __syncthreads();
-  m = sc->red[0];
+  float mm = sc->red_m[0];
 #pragma unroll
-  for (int w = 1; w < NT / 64; ++w) m = fmaxf(m, sc->red[w]);
-  return m;
+  for (int w = 1; w < NT / 64; ++w) mm = fmaxf(mm, sc->red_m[w]);
+  float ll = 0.f;
+#pragma unroll
+  for (int w = 0; w < NT / 64; ++w) {
+    const float mw = sc->red_m[w];
+    ll += (mw == mm) ? sc->red_l[w] : sc->red_l[w] * __expf(mw - mm);
+  }
+  return make_float2(mm, ll);
 }
 
-template <int NT>
-__device__ __forceinline__ float block_sum(float v, TopNScratch<NT>* sc) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) sc->red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  float t = 0.f;
-#pragma unroll
-  for (int w = 0; w < NT / 64; ++w) t += sc->red[w];
-  return t;
+// Softmax partials of keys(0..n-1): (max, sum of exp(key - max)) to every thread.
+// Each thread reduces its own keys around its own maximum, then the pairs merge.
+template <int NT, typename Key>
+__device__ __forceinline__ float2 block_softmax_stats(Key keys, int n, TopNScratch<NT>* sc) {
+  float m = -INFINITY;
+  for (int i = threadIdx.x; i < n; i += NT) m = fmaxf(m, keys(i));
+  float l = 0.f;
+  for (int i = threadIdx.x; i < n; i += NT) l += __expf(keys(i) - m);
+  return block_merge_stats<NT>(m, l, sc);
 }
 
-// Selects the k largest of keys[0..n) (1 <= k <= n), ties to the lower index,
+// Selects the k largest of keys(0..n-1) (1 <= k <= n), ties to the lower index,
 // and calls emit(rank, index, score) for each kept entry, rank ascending with
-// index.  All NT threads of the block must call it; it synchronises inside.
-template <int NT, typename Emit>
-__device__ __forceinline__ void block_topn(const float* keys, int n, int k, TopNScratch<NT>* sc,
+// index.  All NT threads of the block must call it; it synchronises inside and
+// ends with a barrier.  sc->hist is free for the caller once it returns.
+template <int NT, typename Key, typename Emit>
+__device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<NT>* sc,
                                            Emit emit) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int NW = NT / 64;
-  uint32_t T = 0;       // threshold key; with k == n everything is kept
-  int take_eq = 0;
+  uint32_t T = 0;        // with k == n everything is kept: T = 0 is below every key
+  int T_idx = 0x7fffffff;
+  int take_eq = -1;      // >= 0 only on the fallback path: entries == T kept in index order
+
   if (k < n) {
-    // pass 1: key bits 31..21
     for (int i = tid; i < 2048; i += NT) sc->hist[i] = 0;
+    if (tid == 0) sc->list_cnt = 0;
     __syncthreads();
-    for (int i = tid; i < n; i += NT) atomicAdd(&sc->hist[score_key(keys[i]) >> 21], 1u);
+    for (int i = tid; i < n; i += NT) atomicAdd(&sc->hist[score_key(keys(i)) >> 21], 1u);
     __syncthreads();
     find_bin<NT, 2048>(sc, k);
     const uint32_t d1 = (uint32_t)sc->bin;
     const int k1 = sc->rank;
-    __syncthreads();
-    // pass 2: bits 20..10 among the keys of bin d1
-    for (int i = tid; i < 2048; i += NT) sc->hist[i] = 0;
-    __syncthreads();
-    for (int i = tid; i < n; i += NT) {
-      const uint32_t key = score_key(keys[i]);
-      if ((key >> 21) == d1) atomicAdd(&sc->hist[(key >> 10) & 2047u], 1u);
+    const int c1 = (int)sc->hist[d1];
+    if (c1 <= kTopNListCap) {
+      // resolve inside the boundary bin by direct ranking
+      for (int i = tid; i < n; i += NT) {
+        const uint32_t key = score_key(keys(i));
+        if ((key >> 21) == d1) {
+          const int p = atomicAdd(&sc->list_cnt, 1);
+          sc->list_key[p] = key;
+          sc->list_idx[p] = i;
+        }
+      }
+      __syncthreads();
+      for (int e = tid; e < c1; e += NT) {
+        const uint32_t ke = sc->list_key[e];
+        const int ie = sc->list_idx[e];
+        int rank = 0;
+        for (int j = 0; j < c1; ++j) {
+          const uint32_t kj = sc->list_key[j];
+          rank += (kj > ke) || (kj == ke && sc->list_idx[j] < ie);
+        }
+        if (rank == k1 - 1) {
+          sc->thr_key = ke;
+          sc->thr_idx = ie;
+        }
+      }
+      __syncthreads();
+      T = sc->thr_key;
+      T_idx = sc->thr_idx;
+    } else {
+      __syncthreads();  // everyone has read hist[d1]
+      // pass 2: bits 20..10 among the keys of bin d1
+      for (int i = tid; i < 2048; i += NT) sc->hist[i] = 0;
+      __syncthreads();
+      for (int i = tid; i < n; i += NT) {
+        const uint32_t key = score_key(keys(i));
+        if ((key >> 21) == d1) atomicAdd(&sc->hist[(key >> 10) & 2047u], 1u);
+      }
+      __syncthreads();
+      find_bin<NT, 2048>(sc, k1);
+      const uint32_t d2 = (d1 << 11) | (uint32_t)sc->bin;
+      const int k2 = sc->rank;
+      __syncthreads();
+      // pass 3: bits 9..0 among the keys with the 22-bit prefix d2
+      for (int i = tid; i < 1024; i += NT) sc->hist[i] = 0;
+      __syncthreads();
+      for (int i = tid; i < n; i += NT) {
+        const uint32_t key = score_key(keys(i));
+        if ((key >> 10) == d2) atomicAdd(&sc->hist[key & 1023u], 1u);
+      }
+      __syncthreads();
+      find_bin<NT, 1024>(sc, k2);
+      T = (d2 << 10) | (uint32_t)sc->bin;
+      take_eq = sc->rank;
     }
-    __syncthreads();
-    find_bin<NT, 2048>(sc, k1);
-    const uint32_t d2 = (d1 << 11) | (uint32_t)sc->bin;
-    const int k2 = sc->rank;
-    __syncthreads();
-    // pass 3: bits 9..0 among the keys with the 22-bit prefix d2
-    for (int i = tid; i < 1024; i += NT) sc->hist[i] = 0;
-    __syncthreads();
-    for (int i = tid; i < n; i += NT) {
-      const uint32_t key = score_key(keys[i]);
-      if ((key >> 10) == d2) atomicAdd(&sc->hist[key & 1023u], 1u);
-    }
-    __syncthreads();
-    find_bin<NT, 1024>(sc, k2);
-    T = (d2 << 10) | (uint32_t)sc->bin;
-    take_eq = sc->rank;
-  } else {
-    take_eq = n;  // T = 0 is below every key: all entries count as "greater"
   }
 
   // ordered compaction: each wave owns a contiguous range of indices
   const int seg = (((n + NW - 1) / NW) + 63) & ~63;
   const int i_begin = wave * seg;
   const int i_end = (i_begin + seg < n) ? i_begin + seg : n;
-  int cgt = 0, ceq = 0;
+  int ca = 0, cb = 0;  // ca: kept for sure; cb: entries == T (fallback path only)
   for (int i = i_begin + lane; i < i_end; i += 64) {
-    const uint32_t key = score_key(keys[i]);
-    cgt += key > T;
-    ceq += key == T;
+    const uint32_t key = score_key(keys(i));
+    if (take_eq < 0) {
+      ca += (key > T) || (key == T && i <= T_idx);
+    } else {
+      ca += key > T;
+      cb += key == T;
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
-    cgt += __shfl_xor(cgt, o, 64);
-    ceq += __shfl_xor(ceq, o, 64);
+    ca += __shfl_xor(ca, o, 64);
+    cb += __shfl_xor(cb, o, 64);
   }
   __syncthreads();
   if (lane == 0) {
-    sc->seg_gt[wave] = cgt;
-    sc->seg_eq[wave] = ceq;
+    sc->seg_a[wave] = ca;
+    sc->seg_b[wave] = cb;
   }
   __syncthreads();
-  int gt_before = 0, eq_before = 0;
+  int a_before = 0, eq_before = 0;
 #pragma unroll
   for (int w = 0; w < NW; ++w) {
-    gt_before += (w < wave) ? sc->seg_gt[w] : 0;
-    eq_before += (w < wave) ? sc->seg_eq[w] : 0;
+    a_before += (w < wave) ? sc->seg_a[w] : 0;
+    eq_before += (w < wave) ? sc->seg_b[w] : 0;
   }
-  int out_pos = gt_before + (eq_before < take_eq ? eq_before : take_eq);
+  int out_pos = a_before;
+  if (take_eq >= 0) out_pos += eq_before < take_eq ? eq_before : take_eq;
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
   for (int i0 = i_begin; i0 < i_end; i0 += 64) {
     const int i = i0 + lane;
     float v = 0.f;
     bool gt = false, eq = false;
     if (i < i_end) {
-      v = keys[i];
+      v = keys(i);
       const uint32_t key = score_key(v);
       gt = key > T;
       eq = key == T;
     }
-    const uint64_t eq_b = __ballot(eq);
-    const bool sel = gt || (eq && (eq_before + __popcll(eq_b & lt_mask)) < take_eq);
+    bool sel;
+    if (take_eq < 0) {
+      sel = gt || (eq && i <= T_idx);
+    } else {
+      const uint64_t eq_b = __ballot(eq);
+      sel = gt || (eq && (eq_before + __popcll(eq_b & lt_mask)) < take_eq);
+      eq_before += __popcll(eq_b);
+    }
     const uint64_t sel_b = __ballot(sel);
     if (sel) emit(out_pos + __popcll(sel_b & lt_mask), i, v);
     out_pos += __popcll(sel_b);
-    eq_before += __popcll(eq_b);
   }
   __syncthreads();
 }
