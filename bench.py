@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="debug: use fewer layers (invalid as a result)")
     ap.add_argument("--parts", type=int, default=0, help="pipeline parts per layer (0 = library default)")
     ap.add_argument("--gather", choices=["zerocopy", "staged"], default="zerocopy")
+    ap.add_argument("--rows", type=int, default=0, help="fused kernel: positions per workgroup (0 = auto)")
     ap.add_argument("--unfused", action="store_true",
                     help="separate scan / select / gather launches instead of the fused kernel")
     ap.add_argument("--cpu-units", type=int, default=64, help="units in the CPU-oracle sample")
@@ -66,6 +67,7 @@ def main():
     ctx = kc.Context(0, kc.workspace_bytes(wl.B, wl.H, wl.S_cap, wl.N))
     ctx.set_pipeline_parts(a.parts)
     ctx.set_fused(not a.unfused)
+    ctx.set_fused_rows(a.rows)
     mode = kc.GATHER_ZEROCOPY if a.gather == "zerocopy" else kc.GATHER_STAGED
     dt = ki.torch_dtype(wl.dtype)
     lens = wl.seq_lens()

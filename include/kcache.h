@@ -87,9 +87,12 @@ typedef enum {
   KC_OPT_PROFILE = 1,        /* 1: bracket every kernel with HIP events (see
                                 kcache_profile_read); 0: off (default)                */
   KC_OPT_STAGED_THREADS = 2, /* host threads packing rows in KC_GATHER_STAGED mode    */
-  KC_OPT_FUSED = 3           /* 1 (default): KC_GATHER_ZEROCOPY decodes run as one fused
+  KC_OPT_FUSED = 3,          /* 1 (default): KC_GATHER_ZEROCOPY decodes run as one fused
                                 launch per layer whose scores never leave the chip;
                                 0: separate scan / select / gather launches            */
+  KC_OPT_FUSED_ROWS = 4      /* positions scored per workgroup of the fused launch: a
+                                multiple of 512 with rows * (H/Hkv) <= 8192, or 0 =
+                                choose from the shape (default)                        */
 } kc_option;
 
 /* Create a context on `device` (a HIP device ordinal) with a workspace of at

@@ -12,7 +12,7 @@ _HEADER = os.path.join(os.path.dirname(_HERE), "include", "kcache.h")
 KC_F16, KC_BF16 = 0, 1
 GATHER_ZEROCOPY, GATHER_STAGED = 0, 1
 KERNELS = {"kscan": 0, "select": 1, "gather": 2, "store_k": 3, "store_v": 4, "fused": 5}
-OPT_PIPELINE_PARTS, OPT_PROFILE, OPT_STAGED_THREADS, OPT_FUSED = 0, 1, 2, 3
+OPT_PIPELINE_PARTS, OPT_PROFILE, OPT_STAGED_THREADS, OPT_FUSED, OPT_FUSED_ROWS = 0, 1, 2, 3, 4
 
 _c_i32, _c_i64, _c_p, _c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
 
@@ -164,6 +164,9 @@ class Context:
 
     def set_fused(self, on):
         self.set_option(OPT_FUSED, 1 if on else 0)
+
+    def set_fused_rows(self, rows):
+        self.set_option(OPT_FUSED_ROWS, rows)
 
     def set_staged_threads(self, n):
         self.set_option(OPT_STAGED_THREADS, n)

@@ -110,7 +110,7 @@ struct kc_ctx {
   size_t ws_bytes = 0;
   int* flags = nullptr;  // [0] device-check bits, [16] probe sink
   std::string err;
-  int parts = 0, profile = 0, staged_threads = 8, fused = 1;
+  int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0;
   int* counters = nullptr;  // per KV unit arrival tickets of the fused kernel, zero when idle
   size_t counters_n = 0;
   std::vector<ProfRec> pending;
@@ -392,6 +392,17 @@ int kcache_destroy(kc_ctx* c) {
   if (!c) return KC_OK;
   DeviceGuard g(c->device);
   (void)hipDeviceSynchronize();
+#ifdef KC_TIMING
+  {
+    unsigned long long d[9] = {};
+    (void)hipMemcpy(d, c->flags + 32, sizeof d, hipMemcpyDeviceToHost);
+    const double n = d[7] ? (double)d[7] : 1.0, f = d[8] ? (double)d[8] : 1.0;
+    fprintf(stderr, "KC_TIMING us per workgroup (100 MHz clock): scan %.2f stats %.2f topn %.2f handover %.2f | "
+            "per finisher head: load+merge %.2f topn %.2f pull %.2f (workgroups %llu, finisher heads %llu)\n",
+            d[0] / n / 100., d[1] / n / 100., d[2] / n / 100., d[3] / n / 100., d[4] / f / 100., d[5] / f / 100.,
+            d[6] / f / 100., d[7], d[8]);
+  }
+#endif
   delete c->pool;
   for (auto& r : c->pending) {
     (void)hipEventDestroy(r.a);
@@ -430,6 +441,12 @@ int kcache_set_option(kc_ctx* c, int32_t option, int64_t value) {
       return KC_OK;
     case KC_OPT_FUSED:
       c->fused = value != 0;
+      return KC_OK;
+    case KC_OPT_FUSED_ROWS:
+      if (value < 0 || value > kc::kFusedZFloats || value % kc::kFusedThreads != 0)
+        return fail(c, KC_ERR_INVALID_ARG, "fused rows must be 0 or a multiple of %d up to %d",
+                    kc::kFusedThreads, kc::kFusedZFloats);
+      c->fused_rows = (int)value;
       return KC_OK;
     case KC_OPT_STAGED_THREADS:
       if (value < 1 || value > 256)
@@ -509,7 +526,9 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
   const int kv_units = B * Hkv;
   const bool staged = gather_mode == KC_GATHER_STAGED;
   const bool fused = !staged && c->fused;
-  const int R = kc::fused_rows_per_block(kv_units, G, S_cap);
+  const int R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
+                    ? c->fused_rows
+                    : kc::fused_rows_per_block(kv_units, G, S_cap, N);
   const int chunks_cap = (S_cap + R - 1) / R, kk = std::min(N, R);
   const size_t need = fused ? fused_bytes(units, chunks_cap, kk, N) : unfused_bytes(units, S_cap, N);
   if ((rc = ensure_workspace(c, need)) != KC_OK) return rc;

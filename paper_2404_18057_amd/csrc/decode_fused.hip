@@ -31,6 +31,14 @@
 namespace kc {
 namespace {
 
+#ifdef KC_TIMING  // developer build only: per-phase cycle sums in flags[32..]
+#define KC_T(var) const unsigned long long var = wall_clock64()
+#define KC_TADD(slot, val) do { if (threadIdx.x == 0) atomicAdd(reinterpret_cast<unsigned long long*>(a.flags + 32) + (slot), (unsigned long long)(val)); } while (0)
+#else
+#define KC_T(var)
+#define KC_TADD(slot, val)
+#endif
+
 constexpr int FT = kFusedThreads;
 constexpr int FW = FT / 64;
 
@@ -195,6 +203,7 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
   if (row0 >= s) return;
   const int chunks_b = (s + R - 1) / R;
   const int n = (s - row0 < R) ? s - row0 : R;  // valid rows of this chunk
+  KC_T(t0);
 
   // ---------------- 1. scores of R positions for the G heads of the group -> LDS
   {
@@ -239,6 +248,9 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
     }
   }
   __syncthreads();
+  KC_T(t1);
+  KC_TADD(0, t1 - t0);
+  KC_TADD(7, 1);
 
   // ---------------- 2. per head: softmax partials and the chunk's own top-min(N, R)
   float* const stage_f = reinterpret_cast<float*>(sm.sc.hist);
@@ -250,7 +262,10 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
     const float* zg = sm.z + g * R;
     auto key = [&](int i) { return zg[i]; };
     const size_t slot = (size_t)(unit0 + g) * a.chunks_cap + chunk;
+    KC_T(t2a);
     const float2 ml = block_softmax_stats<FT>(key, n, &sm.sc);
+    KC_T(t2b);
+    KC_TADD(1, t2b - t2a);
     if (tid == 0) {
       st_dev(&a.part[slot].x, ml.x);
       st_dev(&a.part[slot].y, ml.y);
@@ -273,7 +288,10 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
       }
       __syncthreads();  // the staging area is the next head's histogram
     }
+    KC_T(t2c);
+    KC_TADD(2, t2c - t2b);
   }
+  KC_T(t3);
 
   // ---------------- 3. the workgroup that completes the unit merges and pulls V
   // Hand-over: every thread waits until its own write-through stores have been
@@ -290,6 +308,8 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
     sm.last = last;
   }
   __syncthreads();
+  KC_T(t4);
+  KC_TADD(3, t4 - t3);
   if (!sm.last) return;
 
   const int n_eff = N < s ? N : s;
@@ -307,21 +327,46 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
     // Everything the merge needs is requested in one batch of bypassing loads.
     const float* cz = a.cand_z + slot0 * kk;
     const int32_t* cp = a.cand_pos + slot0 * kk;
-    float m = -INFINITY, l = 0.f;
-    for (int c = tid; c < chunks_b; c += FT) {
+    // (loads first, uses afterwards: one trip to memory instead of three)
+    constexpr int LB = 8;
+    int32_t* pos_l = reinterpret_cast<int32_t*>(sm.z) + M;
+    float pm = -INFINITY, pl = 0.f;
+    if (tid < chunks_b) {
+      pm = ld_dev(&a.part[slot0 + tid].x);
+      pl = ld_dev(&a.part[slot0 + tid].y);
+    }
+    if (z_in_lds) {
+      for (int i0 = tid; i0 < M; i0 += FT * LB) {
+        float zr[LB];
+        int32_t pr[LB];
+#pragma unroll
+        for (int u = 0; u < LB; ++u) {
+          const int i = i0 + u * FT;
+          zr[u] = (i < M) ? ld_dev(cz + i) : 0.f;
+          pr[u] = (i < M && pos_in_lds) ? ld_dev(cp + i) : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < LB; ++u) {
+          const int i = i0 + u * FT;
+          if (i < M) {
+            sm.z[i] = zr[u];
+            if (pos_in_lds) pos_l[i] = pr[u];
+          }
+        }
+      }
+    }
+    float m = pm, l = pl;
+    for (int c = tid + FT; c < chunks_b; c += FT) {  // more chunks than threads: rare
       const float mc = ld_dev(&a.part[slot0 + c].x), lc = ld_dev(&a.part[slot0 + c].y);
       const float mm = fmaxf(m, mc);
       l = (m == mm ? l : l * __expf(m - mm)) + (mc == mm ? lc : lc * __expf(mc - mm));
       m = mm;
     }
-    int32_t* pos_l = reinterpret_cast<int32_t*>(sm.z) + M;
-    if (z_in_lds)
-      for (int i = tid; i < M; i += FT) sm.z[i] = ld_dev(cz + i);
-    if (pos_in_lds)
-      for (int i = tid; i < M; i += FT) pos_l[i] = ld_dev(cp + i);
     // full-context softmax normaliser from the chunk partials
     const float2 mZ = block_merge_stats<FT>(m, l, &sm.sc);  // barriers: LDS copies are visible
     const float mx = mZ.x, inv_Z = 1.f / mZ.y;
+    KC_T(f1);
+    KC_TADD(4, f1 - t4);
 
     int32_t* iu = a.idx + (size_t)unit * N;
     float* wu = a.w + (size_t)unit * N;
@@ -344,8 +389,13 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
       wu[j] = 0.f;
     }
     // block_topn ended with a barrier: positions and weights are visible to everyone
+    KC_T(f2);
+    KC_TADD(5, f2 - f1);
     pull_and_accumulate<DT>(Vp, stage_out ? stage_i : iu, stage_out ? stage_f : wu, n_eff,
                             a.out + (size_t)unit * kHeadDim, &sm);
+    KC_T(f3);
+    KC_TADD(6, f3 - f2);
+    KC_TADD(8, 1);
   }
 }
 
@@ -364,9 +414,21 @@ hipError_t launch_dt(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
 
 }  // namespace
 
-int fused_rows_per_block(int kv_units, int G, int S_cap) {
-  int R = kFusedZFloats / G;
-  while (R > kFusedThreads && (int64_t)kv_units * ((S_cap + R - 1) / R) < 2048) R /= 2;
+// Positions per workgroup.  Smaller chunks let units finish (and start pulling V)
+// earlier and more evenly; larger chunks mean fewer workgroups paying the fixed
+// selection and hand-over cost, and fewer candidates to merge.  Measured on
+// MI355X, 2048 is the sweet spot for a few hundred units and 4096 once there are
+// enough units that some always finish early.  The merge is fastest when all of a
+// unit's candidates fit its LDS buffer: ceil(S/R) * min(N, R) <= kFusedZFloats.
+int fused_rows_per_block(int kv_units, int G, int S_cap, int N) {
+  const int cap = kFusedZFloats / G;
+  int R = kv_units >= 1024 ? 4096 : 2048;
+  while (R < cap && (int64_t)((S_cap + R - 1) / R) * (N < R ? N : R) > kFusedZFloats) R *= 2;
+  if (R > cap) R = cap;
+  // small problems: more, smaller workgroups as long as the merge still fits
+  while (R > kFusedThreads && (int64_t)kv_units * ((S_cap + R - 1) / R) < 512 &&
+         (int64_t)((S_cap + R / 2 - 1) / (R / 2)) * (N < R / 2 ? N : R / 2) <= kFusedZFloats)
+    R /= 2;
   return R;
 }
 

@@ -73,7 +73,7 @@ struct FusedArgs {
   int kv0;
   float scale;
 };
-int fused_rows_per_block(int kv_units, int G, int S_cap);
+int fused_rows_per_block(int kv_units, int G, int S_cap, int N);
 hipError_t launch_fused(const FusedArgs& a, int dtype, int kv_count, hipStream_t st);
 
 hipError_t launch_probe_read(const void* ptr, size_t bytes, uint32_t* sink, hipStream_t st);

@@ -10,9 +10,10 @@
 //   resolve  the few entries of that bin are copied to an LDS list and ranked
 //            against each other directly (all pairs, tie-break included), which
 //            names the threshold entry without further passes;
-//   fallback a bin too crowded for the list (many equal or nearly equal scores)
-//            goes through two more radix passes (bits 20..10, 9..0) and an
-//            index-ordered count of the entries equal to T;
+//   fallback a bin too crowded for the list is split again on bits 20..10 and
+//            resolved the same way; if even that bin is too crowded (many equal
+//            scores) a third pass on bits 9..0 leaves exactly equal keys, which
+//            are kept in index order by an ordered count;
 //   emit     kept entries are written in ascending index order by an ordered
 //            (ballot + prefix) compaction: nothing depends on the arrival order
 //            of an atomic.
@@ -29,10 +30,10 @@ namespace kc {
 constexpr int kTopNListCap = 512;
 
 template <int NT>
-struct TopNScratch {
+struct alignas(16) TopNScratch {
   uint32_t hist[2048];
-  uint32_t list_key[kTopNListCap];
-  int list_idx[kTopNListCap];
+  uint32_t list_key[kTopNListCap + 4];  // + one padding group of four
+  int list_idx[kTopNListCap + 4];
   int wave_tot[NT / 64];
   int seg_a[NT / 64];
   int seg_b[NT / 64];
@@ -47,6 +48,17 @@ __device__ __forceinline__ uint32_t score_key(float f) {
   uint32_t b = __float_as_uint(f);
   if (b == 0x80000000u) b = 0u;  // -0 and +0 are the same score
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Reads keys(i0), keys(i0 + stride), ... (U of them, 0 beyond n) before any is
+// used, so that the read latencies overlap.
+template <int U, typename Key>
+__device__ __forceinline__ void load_keys(Key keys, int i0, int stride, int n, float (&v)[U]) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int i = i0 + u * stride;
+    v[u] = (i < n) ? keys(i) : 0.f;
+  }
 }
 
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
@@ -135,10 +147,23 @@ __device__ __forceinline__ float2 block_merge_stats(float m, float l, TopNScratc
 // Each thread reduces its own keys around its own maximum, then the pairs merge.
 template <int NT, typename Key>
 __device__ __forceinline__ float2 block_softmax_stats(Key keys, int n, TopNScratch<NT>* sc) {
+  constexpr int U = 8;
   float m = -INFINITY;
-  for (int i = threadIdx.x; i < n; i += NT) m = fmaxf(m, keys(i));
+  for (int i0 = threadIdx.x; i0 < n; i0 += NT * U) {
+    float v[U];
+    load_keys<U>(keys, i0, NT, n, v);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (i0 + u * NT < n) m = fmaxf(m, v[u]);
+  }
   float l = 0.f;
-  for (int i = threadIdx.x; i < n; i += NT) l += __expf(keys(i) - m);
+  for (int i0 = threadIdx.x; i0 < n; i0 += NT * U) {
+    float v[U];
+    load_keys<U>(keys, i0, NT, n, v);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (i0 + u * NT < n) l += __expf(v[u] - m);
+  }
   return block_merge_stats<NT>(m, l, sc);
 }
 
@@ -150,41 +175,52 @@ template <int NT, typename Key, typename Emit>
 __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<NT>* sc,
                                            Emit emit) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  constexpr int NW = NT / 64;
+  constexpr int NW = NT / 64, U = 8;
   uint32_t T = 0;        // with k == n everything is kept: T = 0 is below every key
   int T_idx = 0x7fffffff;
   int take_eq = -1;      // >= 0 only on the fallback path: entries == T kept in index order
 
   if (k < n) {
-    for (int i = tid; i < 2048; i += NT) sc->hist[i] = 0;
-    if (tid == 0) sc->list_cnt = 0;
-    __syncthreads();
-    for (int i = tid; i < n; i += NT) atomicAdd(&sc->hist[score_key(keys(i)) >> 21], 1u);
-    __syncthreads();
-    find_bin<NT, 2048>(sc, k);
-    const uint32_t d1 = (uint32_t)sc->bin;
-    const int k1 = sc->rank;
-    const int c1 = (int)sc->hist[d1];
-    if (c1 <= kTopNListCap) {
-      // resolve inside the boundary bin by direct ranking
-      for (int i = tid; i < n; i += NT) {
-        const uint32_t key = score_key(keys(i));
-        if ((key >> 21) == d1) {
-          const int p = atomicAdd(&sc->list_cnt, 1);
-          sc->list_key[p] = key;
-          sc->list_idx[p] = i;
+    // Entries whose key, shifted right by `shift`, equals `prefix` are copied to
+    // the LDS list and ranked against each other directly (tie-break included);
+    // the entry of rank r - 1 is the threshold.  Needs list_cnt == 0 on entry.
+    auto resolve_in_list = [&](int shift, uint32_t prefix, int count, int r) {
+      if (tid < 4) {  // pad to a multiple of four with entries that rank below everything
+        sc->list_key[count + tid] = 0u;
+        sc->list_idx[count + tid] = 0x7fffffff;
+      }
+      for (int i0 = tid; i0 < n; i0 += NT * U) {
+        float v[U];
+        load_keys<U>(keys, i0, NT, n, v);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int i = i0 + u * NT;
+          const uint32_t key = score_key(v[u]);
+          if (i < n && (key >> shift) == prefix) {
+            const int p = atomicAdd(&sc->list_cnt, 1);
+            sc->list_key[p] = key;
+            sc->list_idx[p] = i;
+          }
         }
       }
       __syncthreads();
-      for (int e = tid; e < c1; e += NT) {
+      const uint4* lk = reinterpret_cast<const uint4*>(sc->list_key);
+      const int4* li = reinterpret_cast<const int4*>(sc->list_idx);
+      const int groups = (count + 3) >> 2;
+      for (int e = tid; e < count; e += NT) {
         const uint32_t ke = sc->list_key[e];
         const int ie = sc->list_idx[e];
         int rank = 0;
-        for (int j = 0; j < c1; ++j) {
-          const uint32_t kj = sc->list_key[j];
-          rank += (kj > ke) || (kj == ke && sc->list_idx[j] < ie);
+#pragma unroll 4
+        for (int j = 0; j < groups; ++j) {  // every lane reads the same 16 bytes: LDS broadcast
+          const uint4 kj = lk[j];
+          const int4 ij = li[j];
+          rank += (kj.x > ke) || (kj.x == ke && ij.x < ie);
+          rank += (kj.y > ke) || (kj.y == ke && ij.y < ie);
+          rank += (kj.z > ke) || (kj.z == ke && ij.z < ie);
+          rank += (kj.w > ke) || (kj.w == ke && ij.w < ie);
         }
-        if (rank == k1 - 1) {
+        if (rank == r - 1) {
           sc->thr_key = ke;
           sc->thr_idx = ie;
         }
@@ -192,31 +228,68 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
       __syncthreads();
       T = sc->thr_key;
       T_idx = sc->thr_idx;
+    };
+
+    // level 1: key bits 31..21
+    for (int i = tid; i < 2048; i += NT) sc->hist[i] = 0;
+    if (tid == 0) sc->list_cnt = 0;
+    __syncthreads();
+    for (int i0 = tid; i0 < n; i0 += NT * U) {
+      float v[U];
+      load_keys<U>(keys, i0, NT, n, v);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (i0 + u * NT < n) atomicAdd(&sc->hist[score_key(v[u]) >> 21], 1u);
+    }
+    __syncthreads();
+    find_bin<NT, 2048>(sc, k);
+    const uint32_t d1 = (uint32_t)sc->bin;
+    const int k1 = sc->rank;
+    const int c1 = (int)sc->hist[d1];
+    if (c1 <= kTopNListCap) {
+      resolve_in_list(21, d1, c1, k1);
     } else {
       __syncthreads();  // everyone has read hist[d1]
-      // pass 2: bits 20..10 among the keys of bin d1
+      // level 2: bits 20..10 among the keys of bin d1
       for (int i = tid; i < 2048; i += NT) sc->hist[i] = 0;
       __syncthreads();
-      for (int i = tid; i < n; i += NT) {
-        const uint32_t key = score_key(keys(i));
-        if ((key >> 21) == d1) atomicAdd(&sc->hist[(key >> 10) & 2047u], 1u);
+      for (int i0 = tid; i0 < n; i0 += NT * U) {
+        float v[U];
+        load_keys<U>(keys, i0, NT, n, v);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const uint32_t key = score_key(v[u]);
+          if (i0 + u * NT < n && (key >> 21) == d1)
+            atomicAdd(&sc->hist[(key >> 10) & 2047u], 1u);
+        }
       }
       __syncthreads();
       find_bin<NT, 2048>(sc, k1);
       const uint32_t d2 = (d1 << 11) | (uint32_t)sc->bin;
       const int k2 = sc->rank;
-      __syncthreads();
-      // pass 3: bits 9..0 among the keys with the 22-bit prefix d2
-      for (int i = tid; i < 1024; i += NT) sc->hist[i] = 0;
-      __syncthreads();
-      for (int i = tid; i < n; i += NT) {
-        const uint32_t key = score_key(keys(i));
-        if ((key >> 10) == d2) atomicAdd(&sc->hist[key & 1023u], 1u);
+      const int c2 = (int)sc->hist[sc->bin];
+      if (c2 <= kTopNListCap) {
+        resolve_in_list(10, d2, c2, k2);
+      } else {
+        __syncthreads();
+        // level 3: bits 9..0 among the keys with the 22-bit prefix d2; what is left
+        // after it are entries with exactly equal keys, kept in index order
+        for (int i = tid; i < 1024; i += NT) sc->hist[i] = 0;
+        __syncthreads();
+        for (int i0 = tid; i0 < n; i0 += NT * U) {
+          float v[U];
+          load_keys<U>(keys, i0, NT, n, v);
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const uint32_t key = score_key(v[u]);
+            if (i0 + u * NT < n && (key >> 10) == d2) atomicAdd(&sc->hist[key & 1023u], 1u);
+          }
+        }
+        __syncthreads();
+        find_bin<NT, 1024>(sc, k2);
+        T = (d2 << 10) | (uint32_t)sc->bin;
+        take_eq = sc->rank;
       }
-      __syncthreads();
-      find_bin<NT, 1024>(sc, k2);
-      T = (d2 << 10) | (uint32_t)sc->bin;
-      take_eq = sc->rank;
     }
   }
 
@@ -224,14 +297,17 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
   const int seg = (((n + NW - 1) / NW) + 63) & ~63;
   const int i_begin = wave * seg;
   const int i_end = (i_begin + seg < n) ? i_begin + seg : n;
-  int ca = 0, cb = 0;  // ca: kept for sure; cb: entries == T (fallback path only)
-  for (int i = i_begin + lane; i < i_end; i += 64) {
-    const uint32_t key = score_key(keys(i));
-    if (take_eq < 0) {
-      ca += (key > T) || (key == T && i <= T_idx);
-    } else {
-      ca += key > T;
-      cb += key == T;
+  int ca = 0, cb = 0;  // ca: kept for sure; cb: entries == T (used on the fallback path)
+  for (int i0 = i_begin + lane; i0 < i_end; i0 += 64 * U) {
+    float v[U];
+    load_keys<U>(keys, i0, 64, i_end, v);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = i0 + u * 64;
+      const uint32_t key = score_key(v[u]);
+      const bool in = i < i_end, gt = key > T, eq = key == T;
+      ca += (in && (gt || (take_eq < 0 && eq && i <= T_idx))) ? 1 : 0;
+      cb += (in && eq) ? 1 : 0;
     }
   }
 #pragma unroll
@@ -254,27 +330,36 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
   int out_pos = a_before;
   if (take_eq >= 0) out_pos += eq_before < take_eq ? eq_before : take_eq;
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
-  for (int i0 = i_begin; i0 < i_end; i0 += 64) {
-    const int i = i0 + lane;
-    float v = 0.f;
-    bool gt = false, eq = false;
-    if (i < i_end) {
-      v = keys(i);
-      const uint32_t key = score_key(v);
-      gt = key > T;
-      eq = key == T;
+  constexpr int EU = 4;
+  for (int i00 = i_begin; i00 < i_end; i00 += 64 * EU) {
+    float vv[EU];
+#pragma unroll
+    for (int u = 0; u < EU; ++u) {
+      const int i = i00 + u * 64 + lane;
+      vv[u] = (i < i_end) ? keys(i) : 0.f;
     }
-    bool sel;
-    if (take_eq < 0) {
-      sel = gt || (eq && i <= T_idx);
-    } else {
-      const uint64_t eq_b = __ballot(eq);
-      sel = gt || (eq && (eq_before + __popcll(eq_b & lt_mask)) < take_eq);
-      eq_before += __popcll(eq_b);
+#pragma unroll
+    for (int u = 0; u < EU; ++u) {
+      const int i = i00 + u * 64 + lane;  // whole 64-groups beyond i_end select nothing
+      const float v = vv[u];
+      bool gt = false, eq = false;
+      if (i < i_end) {
+        const uint32_t key = score_key(v);
+        gt = key > T;
+        eq = key == T;
+      }
+      bool sel;
+      if (take_eq < 0) {
+        sel = gt || (eq && i <= T_idx);
+      } else {
+        const uint64_t eq_b = __ballot(eq);
+        sel = gt || (eq && (eq_before + __popcll(eq_b & lt_mask)) < take_eq);
+        eq_before += __popcll(eq_b);
+      }
+      const uint64_t sel_b = __ballot(sel);
+      if (sel) emit(out_pos + __popcll(sel_b & lt_mask), i, v);
+      out_pos += __popcll(sel_b);
     }
-    const uint64_t sel_b = __ballot(sel);
-    if (sel) emit(out_pos + __popcll(sel_b & lt_mask), i, v);
-    out_pos += __popcll(sel_b);
   }
   __syncthreads();
 }
