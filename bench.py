@@ -42,7 +42,7 @@ def parse():
     ap.add_argument("--unfused", action="store_true",
                     help="separate scan / select / gather launches instead of the fused kernel")
     ap.add_argument("--cpu-units", type=int, default=64, help="units in the CPU-oracle sample")
-    ap.add_argument("--cpu-passes", type=int, default=3, help="oracle passes over the sample")
+    ap.add_argument("--cpu-passes", type=int, default=6, help="oracle passes over the sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true")
     return ap.parse_args()
@@ -51,9 +51,9 @@ def parse():
 def main():
     a = parse()
     if a.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the method's units are independent; "
-              "see DESIGN.md for how it would shard); --gpus %d is not supported" % a.gpus,
-              file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the method's (sequence, head) units are "
+              "independent and would shard by head or by sequence without any exchange); "
+              "--gpus %d is not supported" % a.gpus, file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -163,6 +163,17 @@ def main():
         probes["zerocopy_row_read_GBps"] = ctx.probe_rows(vflat, 1 << 20, iters=3)
         del stage, pinned
 
+    # HBM traffic per launch measured offline with rocprofv3 counters (null if this
+    # workload / path has no committed counter run)
+    traffic = None
+    try:
+        tj = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
+        ent = tj.get("%s/%s" % (wl.name, "fused" if fused_path else "unfused"))
+        if ent and L == wl.L:
+            traffic = ent["fetch_bytes_per_launch"] + ent["write_bytes_per_launch"]
+    except (OSError, ValueError, KeyError):
+        traffic = None
+
     result = {
         "metric": "KCache decode-attn tokens/s",
         "value": wl.B / sec_per_step,
@@ -185,7 +196,7 @@ def main():
             "bound": "hbm", "kernel": "fused_kernel" if fused_path else "kscan_kernel",
             "achieved": scan_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": scan_gbps / HBM_PEAK_GBPS,
-            "traffic": None,
+            "traffic": traffic,
             "bytes_per_launch": k_bytes_layer * L * a.steps / max(scan_n, 1),
             "avg_launch_ms": scan_ms / max(scan_n, 1), "launches": scan_n,
         },
