@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--cpu-passes", type=int, default=6, help="oracle passes over the sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probes", action="store_true")
+    ap.add_argument("--prefill", action="store_true",
+                    help="also time kcache_prefill_store of one layer's whole context (K to HBM, "
+                         "V device-to-host), reported under \"prefill_store\"")
     return ap.parse_args()
 
 
@@ -80,9 +83,13 @@ def main():
     shape = (wl.B, wl.Hkv, wl.S_cap, wl.d)
     T_chunk = min(wl.S_cap, 8192)
     hks = list(range(wl.Hkv))
+    # one pinned allocation for every layer's V (torch rounds each pinned request up to a
+    # power of two: per-layer requests of 1.25 GiB would pin 2 GiB each)
+    layer_elems = int(np.prod(shape))
+    v_all = torch.empty(L * layer_elems, dtype=dt, pin_memory=True)
     for layer in range(L):
         k_cache = torch.empty(shape, dtype=dt, device=dev)
-        v_cache = torch.empty(shape, dtype=dt, pin_memory=True)
+        v_cache = v_all[layer * layer_elems:(layer + 1) * layer_elems].view(shape)
         cache = kc.LayerCache(k_cache, v_cache)
         kt = torch.empty((wl.B, 1, wl.Hkv, wl.d), dtype=dt, device=dev)
         vt = torch.empty((wl.B, 1, wl.Hkv, wl.d), dtype=dt, device=dev)
@@ -217,9 +224,43 @@ def main():
         "probes": probes,
     }
 
+    if a.prefill:
+        result["prefill_store"] = prefill_leg(ctx, kc, wl, caches[0], dev, dt)
+
     if not a.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, L, a.cpu_units, a.cpu_passes, outs, idxs, ws)
     print(json.dumps(result))
+
+
+def prefill_leg(ctx, kc, wl, cache, dev, dt, reps=3):
+    """Store of one layer's full context through kcache_prefill_store, timed as a whole
+    (wall clock, K and V halves overlapped) and per half (HIP events around each kernel).
+    The rows written are the ones already in the cache, so its contents do not change."""
+    T = wl.S_cap
+    k_new = cache.k.permute(0, 2, 1, 3).contiguous()
+    v_new = cache.v.to(dev).permute(0, 2, 1, 3).contiguous()
+    pos = torch.zeros(wl.B, dtype=torch.int32, device=dev)
+    nbytes = k_new.numel() * k_new.element_size()
+    ctx.prefill_store(cache, k_new, v_new, pos)          # warm-up
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    ctx.set_profile(True)
+    ctx.profile_reset()
+    t = time.perf_counter()
+    for _ in range(reps):
+        ctx.prefill_store(cache, k_new, v_new, pos)
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t) / reps
+    k_ms, k_n = ctx.profile_read("store_k")
+    v_ms, v_n = ctx.profile_read("store_v")
+    ctx.set_profile(False)
+    return {"tokens_per_layer": wl.B * T, "bytes_each_of_K_and_V": nbytes,
+            "ms_per_layer": wall * 1e3,
+            "k_to_hbm_GBps": nbytes * k_n / (k_ms * 1e-3) / 1e9 if k_ms else None,
+            "v_to_host_GBps": nbytes * v_n / (v_ms * 1e-3) / 1e9 if v_ms else None,
+            "note": "K half reads and writes HBM (2 x bytes of traffic); V half is posted PCIe "
+                    "writes from the store kernel into the mapped host cache"}
 
 
 def cpu_baseline(wl, L, n_units, passes, outs, idxs, ws):
@@ -232,6 +273,7 @@ def cpu_baseline(wl, L, n_units, passes, outs, idxs, ws):
     cores = len(os.sched_getaffinity(0))
     rng = np.random.default_rng(wl.seed)
     lens = wl.seq_lens()
+    n_units = min(n_units, L * wl.B * wl.H)
     picks = []
     while len(picks) < n_units:
         l, b, h = int(rng.integers(L)), int(rng.integers(wl.B)), int(rng.integers(wl.H))

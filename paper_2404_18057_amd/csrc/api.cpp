@@ -481,7 +481,7 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
     // a decode-step append: too small to be worth a second stream and two event waits
     {
       KernelTimer t(c, KC_KERNEL_STORE_V, st);
-      KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, pos_dev, T, c->flags, st));
+      KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, pos_dev, T, c->flags, 1, st));
     }
     if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, st));
   } else {
@@ -490,7 +490,7 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
     KC_HIP(c, hipStreamWaitEvent(c->store_side, c->ev_fork, 0));
     {
       KernelTimer t(c, KC_KERNEL_STORE_V, c->store_side);
-      KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, pos_dev, T, c->flags, c->store_side));
+      KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, pos_dev, T, c->flags, 1, c->store_side));
     }
     KC_HIP(c, hipEventRecord(c->ev_store, c->store_side));
     c->store_pending = true;
@@ -498,7 +498,7 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
   }
   {
     KernelTimer t(c, KC_KERNEL_STORE_K, st);
-    KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, pos_dev, T, c->flags, st));
+    KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, pos_dev, T, c->flags, 0, st));
   }
   return KC_OK;
 }

@@ -49,7 +49,7 @@ hipError_t launch_gather(const Shape& sh, const void* v, const int32_t* idx, con
 
 // Copy rows of src [B][T][Hkv][d] to dst [B][Hkv][S_cap][d] at pos[b] + t.
 hipError_t launch_store(const Shape& sh, const void* src, void* dst, const int32_t* pos, int T,
-                        int* flags, hipStream_t st);
+                        int* flags, int dst_is_host, hipStream_t st);
 
 // Fused decode kernel (decode_fused.hip): scan + local top-N per chunk, merge,
 // V pull and weighted sum in one launch.

@@ -5,57 +5,76 @@
 //
 // The same kernel serves both halves: for K the destination is HBM, for V it is
 // the mapped host cache, so V rows leave the GPU as posted PCIe writes without
-// a staging copy.  Consecutive 16-lane groups write consecutive positions of
-// one (sequence, KV head), i.e. one contiguous run of destination memory.
+// a staging copy.
+//
+// The V half is link bound (about 57 GB/s).  Posted writes beyond what the link
+// drains back up into the write path they share with HBM traffic: measured on
+// MI355X, a V store of 32 or more workgroups slows a concurrent K store from
+// 2.3 TB/s to 0.5 TB/s and below, while 16 workgroups (256 KiB of writes in
+// flight) leave it untouched and still reach 49 GB/s.  So the host destination
+// gets a small fixed grid that strides over the tiles; that is also what lets the
+// copy hide under the next layer's compute (paper section 3.2, equations (1)-(2)).
 #include "kc_internal.h"
 
 namespace kc {
 namespace {
 
-constexpr int kRowsPerBlock = 64;
+constexpr int kHostStoreBlocks = 20;  // workgroups of a store whose destination is host memory
+constexpr int kTokTile = 4;    // tokens per workgroup
+constexpr int kHeadTile = 16;  // KV heads per workgroup, four per pass
 
+// A workgroup moves a tile of 4 tokens x 16 KV heads.  In each of its four passes
+// the 16 row groups cover 4 tokens x 4 heads: the 4 heads of a token are 1 KiB of
+// contiguous source, the 4 tokens of a head are 1 KiB of contiguous destination.
+// All index arithmetic is 32-bit and done once per workgroup.
 __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ src,
                                                     uint4* __restrict__ dst,
                                                     const int32_t* __restrict__ pos, int B, int T,
-                                                    int Hkv, int S_cap, long long total_rows,
+                                                    int Hkv, int S_cap, int t_tiles, int h_tiles,
+                                                    unsigned total_tiles,
                                                     int* __restrict__ flags) {
   const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
-  const long long r0 = (long long)blockIdx.x * kRowsPerBlock + grp;
-  uint4 v[4];
-  long long d[4];
+  const int ti = grp >> 2, hi = grp & 3;
+  for (unsigned tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+    const unsigned ht = tile % (unsigned)h_tiles;
+    const unsigned rest = tile / (unsigned)h_tiles;
+    const int tt = (int)(rest % (unsigned)t_tiles), b = (int)(rest / (unsigned)t_tiles);
+    const int t = tt * kTokTile + ti;
+    const long long p = (long long)pos[b] + t;
+    const bool t_ok = t < T;
+    const bool p_ok = p >= 0 && p < S_cap;
+    if (t_ok && !p_ok && sub == 0 && hi == 0 && ht == 0) atomicOr(flags, kFlagBadPos);
+    uint4 v[4];
+    bool ok[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const long long r = r0 + i * 16;  // r = (b*Hkv + hk)*T + t
-    d[i] = -1;
-    if (r < total_rows) {
-      const int t = (int)(r % T);
-      const long long bh = r / T;
-      const int hk = (int)(bh % Hkv), b = (int)(bh / Hkv);
-      const long long p = (long long)pos[b] + t;
-      if (p < 0 || p >= S_cap) {
-        if (sub == 0) atomicOr(flags, kFlagBadPos);
-      } else {
-        d[i] = (bh * S_cap + p) * 16 + sub;
-        v[i] = src[(((long long)b * T + t) * Hkv + hk) * 16 + sub];
-      }
+    for (int i = 0; i < 4; ++i) {
+      const int hk = (int)ht * kHeadTile + i * 4 + hi;
+      ok[i] = t_ok && p_ok && hk < Hkv;
+      if (ok[i]) v[i] = src[(((size_t)b * T + t) * Hkv + hk) * 16 + sub];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int hk = (int)ht * kHeadTile + i * 4 + hi;
+      if (ok[i]) dst[(((size_t)b * Hkv + hk) * S_cap + (size_t)p) * 16 + sub] = v[i];
     }
   }
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    if (d[i] >= 0) dst[d[i]] = v[i];
 }
 
 }  // namespace
 
 hipError_t launch_store(const Shape& sh, const void* src, void* dst, const int32_t* pos, int T,
-                        int* flags, hipStream_t st) {
-  const long long rows = (long long)sh.B * T * sh.Hkv;
-  if (rows <= 0) return hipSuccess;
-  const long long blocks = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
-  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+                        int* flags, int dst_is_host, hipStream_t st) {
+  if (sh.B <= 0 || T <= 0 || sh.Hkv <= 0) return hipSuccess;
+  const long long t_tiles = (T + kTokTile - 1) / kTokTile;
+  const long long h_tiles = (sh.Hkv + kHeadTile - 1) / kHeadTile;
+  const long long tiles = (long long)sh.B * t_tiles * h_tiles;
+  if (tiles > 0xffffffffLL) return hipErrorInvalidValue;
+  long long blocks = tiles;
+  const long long cap = dst_is_host ? kHostStoreBlocks : 0x7fffffffLL;
+  if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(store_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
                      static_cast<const uint4*>(src), static_cast<uint4*>(dst), pos, sh.B, T,
-                     sh.Hkv, sh.S_cap, rows, flags);
+                     sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags);
   return hipGetLastError();
 }
 
