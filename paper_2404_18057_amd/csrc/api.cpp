@@ -573,6 +573,7 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
     a.chunks_cap = chunks_cap;
     a.kk = kk;
     a.kv0 = 0;
+    a.kv_count = kv_units;
     a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
     {
       KernelTimer t(c, KC_KERNEL_FUSED, st);

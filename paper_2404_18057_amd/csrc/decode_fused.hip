@@ -40,6 +40,7 @@ namespace {
 #endif
 
 constexpr int FT = kFusedThreads;
+constexpr int kXcds = 8;  // accelerator complex dies of an MI355X
 constexpr int FW = FT / 64;
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
@@ -177,8 +178,18 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
   __shared__ Smem sm;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane & 15, rg = lane >> 4;
-  const int chunk = blockIdx.x % a.chunks_cap;
-  const int ku = a.kv0 + blockIdx.x / a.chunks_cap;
+  // XCD-aware mapping.  Workgroups are handed to the 8 XCDs round-robin in launch
+  // order, so block b runs on XCD b % 8.  All chunks of a KV unit are given to one
+  // XCD (unit u lives on XCD u % 8): a unit then completes as soon as its own XCD
+  // has scanned it, instead of waiting for the slowest of eight, and the merging
+  // and pulling workgroups spread evenly over the XCDs.  (With chunks dealt over all
+  // XCDs one slightly slower XCD ended up finishing - and therefore merging and
+  // pulling - 80 % of all units, which made it slower still.)
+  const int xcd = blockIdx.x % kXcds, in_xcd = blockIdx.x / kXcds;
+  const int chunk = in_xcd % a.chunks_cap;
+  const int ku_rel = xcd + kXcds * (in_xcd / a.chunks_cap);
+  if (ku_rel >= a.kv_count) return;  // padding of the last group of eight units
+  const int ku = a.kv0 + ku_rel;
   const int b = ku / a.Hkv, hk = ku - b * a.Hkv;
   const int R = a.R, N = a.N, kk = a.kk;
   int s = a.seq_lens[b];
@@ -401,7 +412,10 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
 
 template <int DT>
 hipError_t launch_dt(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
-  const dim3 grid((unsigned)(kv_count * a.chunks_cap)), block(FT);
+  // eight XCDs each get ceil(kv_count / 8) units' worth of blocks
+  const long long per_xcd = (long long)((kv_count + kXcds - 1) / kXcds) * a.chunks_cap;
+  if (per_xcd * kXcds > 0x7fffffffLL) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)(per_xcd * kXcds)), block(FT);
   switch (G) {
     case 1: hipLaunchKernelGGL((fused_kernel<DT, 1>), grid, block, 0, st, a); break;
     case 2: hipLaunchKernelGGL((fused_kernel<DT, 2>), grid, block, 0, st, a); break;

@@ -71,6 +71,7 @@ struct FusedArgs {
   int chunks_cap;  // ceil(S_cap / R)
   int kk;          // min(N, R): candidates kept per chunk
   int kv0;
+  int kv_count;    // KV units of this launch
   float scale;
 };
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N);
