@@ -32,8 +32,9 @@ constexpr int kTopNListCap = 512;
 template <int NT>
 struct alignas(16) TopNScratch {
   uint32_t hist[2048];
-  uint32_t list_key[kTopNListCap + 4];  // + one padding group of four
-  int list_idx[kTopNListCap + 4];
+  uint32_t list_key[kTopNListCap];
+  int list_idx[kTopNListCap];
+  int list_rank[kTopNListCap];
   int wave_tot[NT / 64];
   int seg_a[NT / 64];
   int seg_b[NT / 64];
@@ -61,13 +62,61 @@ __device__ __forceinline__ void load_keys(Key keys, int i0, int stride, int n, f
   }
 }
 
+// ---- wavefront primitives on DPP (no LDS traffic, a handful of cycles per step)
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int x) {  // lanes without a source read 0
+  return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) {
+  return __builtin_bit_cast(float, dpp_i<CTRL>(__builtin_bit_cast(int, x)));
+}
+
+// Sum over the 64 lanes, returned to every lane.
+__device__ __forceinline__ int wave_sum(int x) {
+  x += dpp_i<0xB1>(x);   // quad_perm [1,0,3,2]
+  x += dpp_i<0x4E>(x);   // quad_perm [2,3,0,1]
+  x += dpp_i<0x141>(x);  // row_half_mirror
+  x += dpp_i<0x140>(x);  // row_mirror: every lane of a 16-lane row holds the row sum
+  return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) +
+         __builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48);
+}
+__device__ __forceinline__ float wave_sum(float x) {
+  x += dpp_f<0xB1>(x);
+  x += dpp_f<0x4E>(x);
+  x += dpp_f<0x141>(x);
+  x += dpp_f<0x140>(x);
+  const int xi = __builtin_bit_cast(int, x);
+  return (__builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 0)) +
+          __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16))) +
+         (__builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 32)) +
+          __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 48)));
+}
+__device__ __forceinline__ float wave_max(float x) {
+  x = fmaxf(x, dpp_f<0xB1>(x));   // out-of-row sources cannot occur for these four patterns
+  x = fmaxf(x, dpp_f<0x4E>(x));
+  x = fmaxf(x, dpp_f<0x141>(x));
+  x = fmaxf(x, dpp_f<0x140>(x));
+  const int xi = __builtin_bit_cast(int, x);
+  return fmaxf(fmaxf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 0)),
+                     __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 16))),
+               fmaxf(__builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 32)),
+                     __builtin_bit_cast(float, __builtin_amdgcn_readlane(xi, 48))));
+}
+
+__device__ __forceinline__ float wave_min(float x) { return -wave_max(-x); }
+
+// Inclusive prefix sum over the 64 lanes.
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    int n = __shfl_up(v, o, 64);
-    if (lane >= o) v += n;
-  }
-  return v;
+  v += dpp_i<0x111>(v);  // row_shr:1
+  v += dpp_i<0x112>(v);  // row_shr:2
+  v += dpp_i<0x114>(v);  // row_shr:4
+  v += dpp_i<0x118>(v);  // row_shr:8: inclusive scan inside each 16-lane row
+  const int r0 = __builtin_amdgcn_readlane(v, 15), r1 = __builtin_amdgcn_readlane(v, 31),
+            r2 = __builtin_amdgcn_readlane(v, 47);
+  const int row = lane >> 4;
+  return v + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
 }
 
 // Exclusive prefix sum of one int per thread over the block.
@@ -118,16 +167,11 @@ __device__ __forceinline__ void find_bin(TopNScratch<NT>* sc, int k) {
 template <int NT>
 __device__ __forceinline__ float2 block_merge_stats(float m, float l, TopNScratch<NT>* sc) {
   const int tid = threadIdx.x;
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const float m2 = __shfl_xor(m, o, 64), l2 = __shfl_xor(l, o, 64);
-    const float mm = fmaxf(m, m2);
-    l = (m == mm ? l : l * __expf(m - mm)) + (m2 == mm ? l2 : l2 * __expf(m2 - mm));
-    m = mm;
-  }
+  const float wm = wave_max(m);
+  l = wave_sum(m == wm ? l : l * __expf(m - wm));  // (-inf, 0) lanes contribute 0
   __syncthreads();
   if ((tid & 63) == 0) {
-    sc->red_m[tid >> 6] = m;
+    sc->red_m[tid >> 6] = wm;
     sc->red_l[tid >> 6] = l;
   }
   __syncthreads();
@@ -176,54 +220,121 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
                                            Emit emit) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int NW = NT / 64, U = 8;
-  uint32_t T = 0;        // with k == n everything is kept: T = 0 is below every key
+  uint32_t T = 0;        // threshold in normalised key space; with k == n every entry is kept
   int T_idx = 0x7fffffff;
   int take_eq = -1;      // >= 0 only on the fallback path: entries == T kept in index order
+
+  // Keys are taken relative to the smallest one and shifted up so that the largest
+  // uses the top bit: the 2048 first-level bins then span exactly the range of the
+  // scores at hand instead of the whole float line (a few entries per bin near the
+  // threshold instead of hundreds).  The map is strictly increasing, so order and
+  // equality of keys are unchanged.
+  uint32_t kmin = 0;
+  int lz = 0;
+  if (k < n) {
+    float lo = INFINITY, hi = -INFINITY;
+    for (int i0 = tid; i0 < n; i0 += NT * U) {
+      float v[U];
+      load_keys<U>(keys, i0, NT, n, v);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (i0 + u * NT < n) {
+          lo = fminf(lo, v[u]);
+          hi = fmaxf(hi, v[u]);
+        }
+    }
+    lo = wave_min(lo);
+    hi = wave_max(hi);
+    __syncthreads();
+    if (lane == 0) {
+      sc->red_m[wave] = lo;
+      sc->red_l[wave] = hi;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      lo = fminf(lo, sc->red_m[w]);
+      hi = fmaxf(hi, sc->red_l[w]);
+    }
+    kmin = score_key(lo);
+    const uint32_t range = score_key(hi) - kmin;
+    lz = range ? __builtin_clz(range) : 31;
+  }
+  auto nkey = [&](float v) { return (score_key(v) - kmin) << lz; };
 
   if (k < n) {
     // Entries whose key, shifted right by `shift`, equals `prefix` are copied to
     // the LDS list and ranked against each other directly (tie-break included);
     // the entry of rank r - 1 is the threshold.  Needs list_cnt == 0 on entry.
     auto resolve_in_list = [&](int shift, uint32_t prefix, int count, int r) {
-      if (tid < 4) {  // pad to a multiple of four with entries that rank below everything
-        sc->list_key[count + tid] = 0u;
-        sc->list_idx[count + tid] = 0x7fffffff;
+      // pad to a multiple of 16 with entries that rank below everything, and clear
+      // the rank accumulators
+      const int padded = (count + 15) & ~15;
+      for (int e = tid; e < padded; e += NT) {
+        if (e >= count) {
+          sc->list_key[e] = 0u;
+          sc->list_idx[e] = 0x7fffffff;
+        }
+        sc->list_rank[e] = 0;
       }
-      for (int i0 = tid; i0 < n; i0 += NT * U) {
+      // append matching entries; one LDS atomic per wave and step, not per entry
+      const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+      for (int i0 = tid; i0 - lane < n; i0 += NT * U) {  // whole waves stay in the loop
         float v[U];
         load_keys<U>(keys, i0, NT, n, v);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           const int i = i0 + u * NT;
-          const uint32_t key = score_key(v[u]);
-          if (i < n && (key >> shift) == prefix) {
-            const int p = atomicAdd(&sc->list_cnt, 1);
-            sc->list_key[p] = key;
-            sc->list_idx[p] = i;
+          const uint32_t key = nkey(v[u]);
+          const bool hit = i < n && (key >> shift) == prefix;
+          const uint64_t hits = __ballot(hit);
+          if (hits) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&sc->list_cnt, __popcll(hits));
+            base = __builtin_amdgcn_readfirstlane(base);
+            if (hit) {
+              const int p = base + __popcll(hits & lt_mask);
+              sc->list_key[p] = key;
+              sc->list_idx[p] = i;
+            }
           }
         }
       }
       __syncthreads();
+      // all-pairs ranking, spread over the whole block: thread t takes entry
+      // t % padded and every (NT / padded)-th group of four of the others
       const uint4* lk = reinterpret_cast<const uint4*>(sc->list_key);
       const int4* li = reinterpret_cast<const int4*>(sc->list_idx);
-      const int groups = (count + 3) >> 2;
-      for (int e = tid; e < count; e += NT) {
+      const int groups = padded >> 2;
+      const int parts = NT / padded;           // >= 1 because padded <= kTopNListCap <= NT
+      const int e = tid % padded, part = tid / padded;
+      if (part < parts) {
         const uint32_t ke = sc->list_key[e];
         const int ie = sc->list_idx[e];
         int rank = 0;
-#pragma unroll 4
-        for (int j = 0; j < groups; ++j) {  // every lane reads the same 16 bytes: LDS broadcast
-          const uint4 kj = lk[j];
-          const int4 ij = li[j];
-          rank += (kj.x > ke) || (kj.x == ke && ij.x < ie);
-          rank += (kj.y > ke) || (kj.y == ke && ij.y < ie);
-          rank += (kj.z > ke) || (kj.z == ke && ij.z < ie);
-          rank += (kj.w > ke) || (kj.w == ke && ij.w < ie);
+        for (int j0 = part; j0 < groups; j0 += parts * 4) {
+          uint4 kj[4];
+          int4 ij[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {  // loads first: their latencies overlap
+            const int j = j0 + q * parts;
+            kj[q] = (j < groups) ? lk[j] : make_uint4(0, 0, 0, 0);
+            ij[q] = (j < groups) ? li[j] : make_int4(0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff);
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            rank += (kj[q].x > ke) || (kj[q].x == ke && ij[q].x < ie);
+            rank += (kj[q].y > ke) || (kj[q].y == ke && ij[q].y < ie);
+            rank += (kj[q].z > ke) || (kj[q].z == ke && ij[q].z < ie);
+            rank += (kj[q].w > ke) || (kj[q].w == ke && ij[q].w < ie);
+          }
         }
-        if (rank == r - 1) {
-          sc->thr_key = ke;
-          sc->thr_idx = ie;
-        }
+        if (rank) atomicAdd(&sc->list_rank[e], rank);
+      }
+      __syncthreads();
+      if (tid < count && sc->list_rank[tid] == r - 1) {
+        sc->thr_key = sc->list_key[tid];
+        sc->thr_idx = sc->list_idx[tid];
       }
       __syncthreads();
       T = sc->thr_key;
@@ -239,7 +350,7 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
       load_keys<U>(keys, i0, NT, n, v);
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        if (i0 + u * NT < n) atomicAdd(&sc->hist[score_key(v[u]) >> 21], 1u);
+        if (i0 + u * NT < n) atomicAdd(&sc->hist[nkey(v[u]) >> 21], 1u);
     }
     __syncthreads();
     find_bin<NT, 2048>(sc, k);
@@ -258,7 +369,7 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
         load_keys<U>(keys, i0, NT, n, v);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const uint32_t key = score_key(v[u]);
+          const uint32_t key = nkey(v[u]);
           if (i0 + u * NT < n && (key >> 21) == d1)
             atomicAdd(&sc->hist[(key >> 10) & 2047u], 1u);
         }
@@ -281,7 +392,7 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
           load_keys<U>(keys, i0, NT, n, v);
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-            const uint32_t key = score_key(v[u]);
+            const uint32_t key = nkey(v[u]);
             if (i0 + u * NT < n && (key >> 10) == d2) atomicAdd(&sc->hist[key & 1023u], 1u);
           }
         }
@@ -304,17 +415,14 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int i = i0 + u * 64;
-      const uint32_t key = score_key(v[u]);
+      const uint32_t key = nkey(v[u]);
       const bool in = i < i_end, gt = key > T, eq = key == T;
       ca += (in && (gt || (take_eq < 0 && eq && i <= T_idx))) ? 1 : 0;
       cb += (in && eq) ? 1 : 0;
     }
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    ca += __shfl_xor(ca, o, 64);
-    cb += __shfl_xor(cb, o, 64);
-  }
+  ca = wave_sum(ca);
+  cb = wave_sum(cb);
   __syncthreads();
   if (lane == 0) {
     sc->seg_a[wave] = ca;
@@ -344,7 +452,7 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
       const float v = vv[u];
       bool gt = false, eq = false;
       if (i < i_end) {
-        const uint32_t key = score_key(v);
+        const uint32_t key = nkey(v);
         gt = key > T;
         eq = key == T;
       }
