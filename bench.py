@@ -97,14 +97,18 @@ def main():
             k, v = ki.gen_kv_units(wl, layer, b, hks, wl.S_cap, dev)
             sub = kc.LayerCache(k_cache[b:b + 1], v_cache[b:b + 1])
             zero = torch.zeros(1, dtype=torch.int32, device=dev)
+            alive = []   # the V half runs on the library's side stream: inputs must outlive it
             for t in range(0, wl.S_cap, T_chunk):
                 kn = k[:, t:t + T_chunk].permute(1, 0, 2).unsqueeze(0).contiguous()
                 vn = v[:, t:t + T_chunk].permute(1, 0, 2).unsqueeze(0).contiguous()
-                ctx.prefill_store(sub, kn, vn, zero + t)
+                pos = zero + t
+                ctx.prefill_store(sub, kn, vn, pos)
+                alive.append((kn, vn, pos))
             kt[b, 0] = k[:, lens[b] - 1]
             vt[b, 0] = v[:, lens[b] - 1]
             ctx.synchronize()
             torch.cuda.synchronize()
+            del alive
         caches.append(cache)
         qs.append(ki.gen_q(wl, layer, dev))
         k_tok.append(kt)

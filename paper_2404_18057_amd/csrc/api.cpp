@@ -478,27 +478,31 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
   hipStream_t st = (hipStream_t)stream;
   const kc::Shape sh{cache->B, 0, cache->Hkv, cache->S_cap, 0, cache->dtype};
   if ((int64_t)cache->B * T * cache->Hkv <= 4096) {
-    // a decode-step append: too small to be worth a second stream and two event waits
+    // a decode-step append: K and V rows in one small launch on the caller's stream
+    // (too little data to be worth a second stream and two event waits)
     {
-      KernelTimer t(c, KC_KERNEL_STORE_V, st);
-      KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, pos_dev, T, c->flags, 1, st));
+      KernelTimer t(c, KC_KERNEL_STORE_K, st);
+      KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, v_new_dev, v_map, pos_dev, T,
+                                 c->flags, 1, st));
     }
     if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, st));
-  } else {
-    // V first: the side stream starts as soon as the inputs are ready on `st`
-    KC_HIP(c, hipEventRecord(c->ev_fork, st));
-    KC_HIP(c, hipStreamWaitEvent(c->store_side, c->ev_fork, 0));
-    {
-      KernelTimer t(c, KC_KERNEL_STORE_V, c->store_side);
-      KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, pos_dev, T, c->flags, 1, c->store_side));
-    }
-    KC_HIP(c, hipEventRecord(c->ev_store, c->store_side));
-    c->store_pending = true;
-    if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, c->store_side));
+    return KC_OK;
   }
+  // V first: the side stream starts as soon as the inputs are ready on `st`
+  KC_HIP(c, hipEventRecord(c->ev_fork, st));
+  KC_HIP(c, hipStreamWaitEvent(c->store_side, c->ev_fork, 0));
+  {
+    KernelTimer t(c, KC_KERNEL_STORE_V, c->store_side);
+    KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, nullptr, nullptr, pos_dev, T, c->flags, 1,
+                               c->store_side));
+  }
+  KC_HIP(c, hipEventRecord(c->ev_store, c->store_side));
+  c->store_pending = true;
+  if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, c->store_side));
   {
     KernelTimer t(c, KC_KERNEL_STORE_K, st);
-    KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, pos_dev, T, c->flags, 0, st));
+    KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, nullptr, nullptr, pos_dev, T,
+                               c->flags, 0, st));
   }
   return KC_OK;
 }

@@ -429,14 +429,14 @@ hipError_t launch_dt(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
 }  // namespace
 
 // Positions per workgroup.  Smaller chunks let units finish (and start pulling V)
-// earlier and more evenly; larger chunks mean fewer workgroups paying the fixed
-// selection and hand-over cost, and fewer candidates to merge.  Measured on
-// MI355X, 2048 is the sweet spot for a few hundred units and 4096 once there are
-// enough units that some always finish early.  The merge is fastest when all of a
-// unit's candidates fit its LDS buffer: ceil(S/R) * min(N, R) <= kFusedZFloats.
+// earlier and more evenly, and leave fewer units in flight when the scan ends;
+// larger chunks mean fewer workgroups paying the fixed selection and hand-over
+// cost, and fewer candidates to merge.  Measured on MI355X, 1024 is the sweet spot
+// as long as all of a unit's candidates fit the merging workgroup's LDS buffer,
+// ceil(S/R) * min(N, R) <= kFusedZFloats; otherwise the smallest R that fits.
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N) {
   const int cap = kFusedZFloats / G;
-  int R = kv_units >= 1024 ? 4096 : 2048;
+  int R = 1024;
   while (R < cap && (int64_t)((S_cap + R - 1) / R) * (N < R ? N : R) > kFusedZFloats) R *= 2;
   if (R > cap) R = cap;
   // small problems: more, smaller workgroups as long as the merge still fits

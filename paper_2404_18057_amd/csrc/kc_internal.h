@@ -47,9 +47,10 @@ hipError_t launch_select(const Shape& sh, const float* z, const int32_t* seq_len
 hipError_t launch_gather(const Shape& sh, const void* v, const int32_t* idx, const float* w,
                          float* out, int u0, int count, int packed, hipStream_t st);
 
-// Copy rows of src [B][T][Hkv][d] to dst [B][Hkv][S_cap][d] at pos[b] + t.
-hipError_t launch_store(const Shape& sh, const void* src, void* dst, const int32_t* pos, int T,
-                        int* flags, int dst_is_host, hipStream_t st);
+// Copy rows of src [B][T][Hkv][d] to dst [B][Hkv][S_cap][d] at pos[b] + t; src2 / dst2
+// (may be null) are a second pair moved in the same launch.
+hipError_t launch_store(const Shape& sh, const void* src, void* dst, const void* src2, void* dst2,
+                        const int32_t* pos, int T, int* flags, int dst_is_host, hipStream_t st);
 
 // Fused decode kernel (decode_fused.hip): scan + local top-N per chunk, merge,
 // V pull and weighted sum in one launch.

@@ -27,8 +27,13 @@ constexpr int kHeadTile = 16;  // KV heads per workgroup, four per pass
 // the 16 row groups cover 4 tokens x 4 heads: the 4 heads of a token are 1 KiB of
 // contiguous source, the 4 tokens of a head are 1 KiB of contiguous destination.
 // All index arithmetic is 32-bit and done once per workgroup.
+//
+// src2 / dst2, when not null, are a second tensor pair moved with the same
+// indices (the K and V rows of a decode-step append in one launch).
 __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ src,
                                                     uint4* __restrict__ dst,
+                                                    const uint4* __restrict__ src2,
+                                                    uint4* __restrict__ dst2,
                                                     const int32_t* __restrict__ pos, int B, int T,
                                                     int Hkv, int S_cap, int t_tiles, int h_tiles,
                                                     unsigned total_tiles,
@@ -44,26 +49,30 @@ __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ sr
     const bool t_ok = t < T;
     const bool p_ok = p >= 0 && p < S_cap;
     if (t_ok && !p_ok && sub == 0 && hi == 0 && ht == 0) atomicOr(flags, kFlagBadPos);
-    uint4 v[4];
+    uint4 v[4], v2[4];
     bool ok[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int hk = (int)ht * kHeadTile + i * 4 + hi;
       ok[i] = t_ok && p_ok && hk < Hkv;
-      if (ok[i]) v[i] = src[(((size_t)b * T + t) * Hkv + hk) * 16 + sub];
+      const size_t from = (((size_t)b * T + t) * Hkv + hk) * 16 + sub;
+      if (ok[i]) v[i] = src[from];
+      if (ok[i] && src2) v2[i] = src2[from];
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int hk = (int)ht * kHeadTile + i * 4 + hi;
-      if (ok[i]) dst[(((size_t)b * Hkv + hk) * S_cap + (size_t)p) * 16 + sub] = v[i];
+      const size_t to = (((size_t)b * Hkv + hk) * S_cap + (size_t)p) * 16 + sub;
+      if (ok[i]) dst[to] = v[i];
+      if (ok[i] && src2) dst2[to] = v2[i];
     }
   }
 }
 
 }  // namespace
 
-hipError_t launch_store(const Shape& sh, const void* src, void* dst, const int32_t* pos, int T,
-                        int* flags, int dst_is_host, hipStream_t st) {
+hipError_t launch_store(const Shape& sh, const void* src, void* dst, const void* src2, void* dst2,
+                        const int32_t* pos, int T, int* flags, int dst_is_host, hipStream_t st) {
   if (sh.B <= 0 || T <= 0 || sh.Hkv <= 0) return hipSuccess;
   const long long t_tiles = (T + kTokTile - 1) / kTokTile;
   const long long h_tiles = (sh.Hkv + kHeadTile - 1) / kHeadTile;
@@ -73,7 +82,8 @@ hipError_t launch_store(const Shape& sh, const void* src, void* dst, const int32
   const long long cap = dst_is_host ? kHostStoreBlocks : 0x7fffffffLL;
   if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(store_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                     static_cast<const uint4*>(src), static_cast<uint4*>(dst), pos, sh.B, T,
+                     static_cast<const uint4*>(src), static_cast<uint4*>(dst),
+                     static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,
                      sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags);
   return hipGetLastError();
 }
