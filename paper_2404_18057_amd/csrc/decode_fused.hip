@@ -283,7 +283,7 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
     }
     float* cz = a.cand_z + slot * kk;
     int32_t* cp = a.cand_pos + slot * kk;
-    block_topn<FT>(key, n, k_loc, &sm.sc, [&](int r, int i, float v) {
+    block_topn<FT, false>(key, n, k_loc, &sm.sc, [&](int r, int i, float v) {
       if (stage_loc) {  // collect in LDS, then write whole lines
         stage_f[r] = v;
         stage_i[r] = row0 + i;
@@ -392,9 +392,9 @@ __global__ __launch_bounds__(FT) void fused_kernel(FusedArgs a) {
       }
     };
     if (z_in_lds)
-      block_topn<FT>([&](int i) { return sm.z[i]; }, M, n_eff, &sm.sc, emit);
+      block_topn<FT, true>([&](int i) { return sm.z[i]; }, M, n_eff, &sm.sc, emit);
     else  // more candidates than the LDS buffer holds: read them around the L2 every pass
-      block_topn<FT>([&](int i) { return ld_dev(cz + i); }, M, n_eff, &sm.sc, emit);
+      block_topn<FT, true>([&](int i) { return ld_dev(cz + i); }, M, n_eff, &sm.sc, emit);
     for (int j = n_eff + tid; j < N; j += FT) {
       iu[j] = -1;
       wu[j] = 0.f;

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(NT) void select_kernel(const float* __restrict__ z,
   auto key = [&](int t) { return zr[t]; };
   const float2 ml = block_softmax_stats<NT>(key, s, &sc);
   const float m = ml.x, inv_Z = 1.f / ml.y;
-  block_topn<NT>(key, s, n_eff, &sc, [&](int r, int t, float v) {
+  block_topn<NT, false>(key, s, n_eff, &sc, [&](int r, int t, float v) {
     iu[r] = t;
     wu[r] = expf(v - m) * inv_Z;
   });

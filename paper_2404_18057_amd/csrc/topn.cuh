@@ -215,7 +215,11 @@ __device__ __forceinline__ float2 block_softmax_stats(Key keys, int n, TopNScrat
 // and calls emit(rank, index, score) for each kept entry, rank ascending with
 // index.  All NT threads of the block must call it; it synchronises inside and
 // ends with a barrier.  sc->hist is free for the caller once it returns.
-template <int NT, typename Key, typename Emit>
+//
+// NORMALIZE: take keys relative to the smallest one (see below).  Worth its extra
+// pass when the scores are a pre-filtered, narrow set (the merge of chunk lists);
+// for the raw scores of a chunk the plain float key space resolves well enough.
+template <int NT, bool NORMALIZE, typename Key, typename Emit>
 __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<NT>* sc,
                                            Emit emit) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -231,7 +235,7 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
   // equality of keys are unchanged.
   uint32_t kmin = 0;
   int lz = 0;
-  if (k < n) {
+  if (NORMALIZE && k < n) {
     float lo = INFINITY, hi = -INFINITY;
     for (int i0 = tid; i0 < n; i0 += NT * U) {
       float v[U];
