@@ -41,6 +41,11 @@ def _load():
         lib.kcache_oracle_decode.argtypes = [c_p, c_p, c_p, ctypes.c_int, c_i32, c_i32, c_i32,
                                              c_i32, c_i32, c_p, c_i32, c_p, c_p, c_p, ctypes.c_int]
         lib.kcache_oracle_decode.restype = ctypes.c_int
+        lib.kcache_oracle_full_unit.argtypes = [c_p, c_p, c_p, ctypes.c_int, c_i32, c_i32, c_p, c_p]
+        lib.kcache_oracle_full_unit.restype = ctypes.c_int
+        lib.kcache_oracle_full_attention.argtypes = [c_p, c_p, c_p, ctypes.c_int, c_i32, c_i32,
+                                                     c_i32, c_i32, c_i32, c_p, c_p, ctypes.c_int]
+        lib.kcache_oracle_full_attention.restype = ctypes.c_int
         lib.kcache_oracle_store.argtypes = [c_p, c_p, c_p, c_p, c_p, c_i32, c_i32, c_i32, c_i32,
                                             c_i32]
         lib.kcache_oracle_store.restype = ctypes.c_int
@@ -110,6 +115,38 @@ def decode_attention(q, K, V, dtype, seq_lens, N, nthreads=1):
     if rc != 0:
         raise ValueError("kcache_oracle_decode rejected its arguments")
     return out, idx, w
+
+
+def full_unit(q, K, V, dtype, want_p=False):
+    """Conventional attention of one (sequence, head) unit: softmax(q K^T / sqrt(d)) V.
+
+    Returns out [d] f64, or (out, p [s]) with want_p."""
+    q, K, V = _u16(q), _u16(K), _u16(V)
+    s, d = K.shape
+    assert q.shape == (d,) and V.shape == (s, d)
+    out = np.empty(d, np.float64)
+    p = np.empty(s, np.float64) if want_p else None
+    rc = _load().kcache_oracle_full_unit(_ptr(q), _ptr(K), _ptr(V), dtype, s, d, _ptr(out),
+                                         _ptr(p) if want_p else None)
+    if rc != 0:
+        raise ValueError("kcache_oracle_full_unit rejected its arguments")
+    return (out, p) if want_p else out
+
+
+def full_attention(q, K, V, dtype, seq_lens, nthreads=1):
+    """Conventional attention, one layer.  Layouts as decode_attention; returns out [B][H][d] f64."""
+    q, K, V = _u16(q), _u16(K), _u16(V)
+    B, H, d = q.shape
+    Bk, Hkv, S_cap, dk = K.shape
+    assert (Bk, dk) == (B, d) and V.shape == K.shape
+    seq_lens = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    assert seq_lens.shape == (B,)
+    out = np.empty((B, H, d), np.float64)
+    rc = _load().kcache_oracle_full_attention(_ptr(q), _ptr(K), _ptr(V), dtype, B, H, Hkv, S_cap,
+                                              d, _ptr(seq_lens), _ptr(out), int(nthreads))
+    if rc != 0:
+        raise ValueError("kcache_oracle_full_attention rejected its arguments")
+    return out
 
 
 def store(k_cache, v_cache, k_new, v_new, pos):

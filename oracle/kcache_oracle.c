@@ -31,7 +31,9 @@
  * invariance, N = s against a library attention routine, brute-force sort,
  * uniform-score closed form, two-score logistic closed form, GQA by head
  * repetition, ragged batch by independent calls, 16-bit decode against a
- * library decode.  The no-renormalisation reading itself is "parity unpinned"
+ * library decode; the conventional-attention routine against the same library
+ * routine, a uniform-score closed form and the N = s case of the top-N routine.
+ * The no-renormalisation reading itself is "parity unpinned"
  * by the paper: only the literal formula fixes it.
  */
 #include <math.h>
@@ -205,6 +207,72 @@ int kcache_oracle_decode(const uint16_t* q, const uint16_t* K, const uint16_t* V
     int rc = kcache_oracle_unit(q + (size_t)u * d, K + kv_off, V + kv_off, dtype, seq_lens[b], d, N,
                                 out + (size_t)u * d, idx + (size_t)u * N, w + (size_t)u * N, NULL,
                                 NULL);
+    if (rc != 0) {
+#pragma omp atomic write
+      status = -1;
+    }
+  }
+  return status;
+}
+
+/*
+ * Conventional decode attention, the baseline the method is compared with
+ * (paper section 2: Attention(Q, K, V) = softmax(Q K^T / sqrt(d_h)) V; Table 1
+ * rows "S = softmax(Q K^T / sqrt(d_h))" and "A = S V"; section 3.1 and the
+ * caption of Table 2: the first L layers keep their V cache in HBM).  Every
+ * position contributes; nothing is selected.  Written out on its own, not as a
+ * call of the top-N routine, so that the two can be checked against each other.
+ *   q [d], K [s][d], V [s][d] stored 16-bit values; out [d] double
+ *   p_out [s] optional (may be NULL): the softmax
+ * Returns 0, or -1 on bad arguments / allocation failure.
+ */
+int kcache_oracle_full_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, int dtype,
+                            int32_t s, int32_t d, double* out, double* p_out) {
+  if (!q || !K || !V || !out || s < 1 || d < 1) return -1;
+  double* z = (double*)malloc(sizeof(double) * (size_t)s);
+  if (!z) return -1;
+  const double inv_sqrt_d = 1.0 / sqrt((double)d);
+  for (int32_t t = 0; t < s; ++t) {
+    double acc = 0.0;
+    for (int32_t c = 0; c < d; ++c)
+      acc += kco_decode(q[c], dtype) * kco_decode(K[(size_t)t * d + c], dtype);
+    z[t] = acc * inv_sqrt_d;
+  }
+  double m = z[0];
+  for (int32_t t = 1; t < s; ++t)
+    if (z[t] > m) m = z[t];
+  double Z = 0.0;
+  for (int32_t t = 0; t < s; ++t) Z += exp(z[t] - m);
+  for (int32_t c = 0; c < d; ++c) out[c] = 0.0;
+  for (int32_t t = 0; t < s; ++t) {
+    const double p = exp(z[t] - m) / Z;
+    if (p_out) p_out[t] = p;
+    for (int32_t c = 0; c < d; ++c) out[c] += p * kco_decode(V[(size_t)t * d + c], dtype);
+  }
+  free(z);
+  return 0;
+}
+
+/*
+ * Conventional attention for one layer, whole batch; same layouts, GQA mapping
+ * and threading as kcache_oracle_decode.  out [B][H][d] double.
+ */
+int kcache_oracle_full_attention(const uint16_t* q, const uint16_t* K, const uint16_t* V,
+                                 int dtype, int32_t B, int32_t H, int32_t Hkv, int32_t S_cap,
+                                 int32_t d, const int32_t* seq_lens, double* out, int nthreads) {
+  if (!q || !K || !V || !seq_lens || !out) return -1;
+  if (B < 1 || H < 1 || Hkv < 1 || H % Hkv != 0 || S_cap < 1 || d < 1) return -1;
+  for (int32_t b = 0; b < B; ++b)
+    if (seq_lens[b] < 1 || seq_lens[b] > S_cap) return -1;
+  const int32_t G = H / Hkv;
+  int status = 0;
+  int64_t units = (int64_t)B * H;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 1 ? nthreads : 1)
+  for (int64_t u = 0; u < units; ++u) {
+    int32_t b = (int32_t)(u / H), h = (int32_t)(u % H);
+    size_t kv_off = ((size_t)b * Hkv + h / G) * (size_t)S_cap * d;
+    int rc = kcache_oracle_full_unit(q + (size_t)u * d, K + kv_off, V + kv_off, dtype,
+                                     seq_lens[b], d, out + (size_t)u * d, NULL);
     if (rc != 0) {
 #pragma omp atomic write
       status = -1;

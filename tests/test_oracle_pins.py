@@ -345,3 +345,79 @@ def test_store_rejects_overflowing_positions():
         oracle.store(kc, vc, new, new, np.array([2], np.int32))
     with pytest.raises(ValueError):
         oracle.store(kc, vc, new, new, np.array([-1], np.int32))
+
+
+# ---------------------------------------------------------------- conventional attention
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("s,d", [(1, 64), (33, 128), (700, 128)])
+def test_conventional_attention_equals_library_attention(dtype, s, d):
+    # section 2: softmax(q K^T / sqrt(d_h)) V; library routine: torch SDPA in fp64.
+    # Catches a wrong scale, a missing max shift going wrong, K / V swapped, a
+    # transposed operand.
+    rng = np.random.default_rng(90 + s)
+    q, K, V = rand_unit(rng, s, d, dtype, scale=1.5)
+    out, p = oracle.full_unit(q, K, V, dtype, want_p=True)
+    tq = torch.from_numpy(back(q, dtype)).reshape(1, 1, 1, d)
+    tk = torch.from_numpy(back(K, dtype)).reshape(1, 1, s, d)
+    tv = torch.from_numpy(back(V, dtype)).reshape(1, 1, s, d)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).reshape(d).numpy()
+    assert np.allclose(out, ref, rtol=1e-11, atol=1e-13)
+    assert abs(p.sum() - 1.0) < 1e-12 and (p > 0).all()
+
+
+def test_conventional_attention_uniform_scores_is_the_mean_of_v():
+    # identical K rows => p = 1/s => out = mean of the V rows (closed form)
+    rng = np.random.default_rng(91)
+    s, d = 48, 16
+    q = bits(rng.standard_normal(d))
+    K = np.tile(bits(rng.standard_normal(d)), (s, 1))
+    Vf = np.round(rng.standard_normal((s, d)) * 16) / 16
+    out, p = oracle.full_unit(q, K, bits(Vf), F16, want_p=True)
+    assert np.allclose(p, 1.0 / s, rtol=1e-14)
+    assert np.allclose(out, Vf.mean(0), rtol=0, atol=1e-14)
+
+
+def test_conventional_attention_two_scores_closed_form():
+    # two positions with scores z0, z1: p0 = 1 / (1 + exp(z1 - z0)); pins sign and scale
+    d = 4
+    q = bits(np.array([2.0, 0.0, 0.0, 0.0]))
+    K = bits(np.array([[1.0, 0, 0, 0], [-0.5, 0, 0, 0]]))
+    V = bits(np.array([[1.0, 0, 0, 0], [0, 1.0, 0, 0]]))
+    out = oracle.full_unit(q, K, V, F16)
+    z0, z1 = 2.0 * 1.0 / 2.0, 2.0 * -0.5 / 2.0
+    p0 = 1.0 / (1.0 + math.exp(z1 - z0))
+    assert np.allclose(out, [p0, 1.0 - p0, 0, 0], rtol=1e-14, atol=0)
+
+
+def test_conventional_attention_is_the_n_equals_s_case_of_kcache():
+    # section 3.1: with N = s nothing is dropped; two separately written routines agree
+    rng = np.random.default_rng(92)
+    q, K, V = rand_unit(rng, 257, 128, BF16)
+    a = oracle.full_unit(q, K, V, BF16)
+    b = oracle.decode_unit(q, K, V, BF16, 257)["out"]
+    assert np.allclose(a, b, rtol=1e-12, atol=1e-14)
+
+
+def test_conventional_attention_batch_gqa_ragged_and_padding():
+    # batch routine = per-unit routine on the right KV head and the first s_b rows;
+    # rows beyond s_b must not matter
+    rng = np.random.default_rng(93)
+    B, H, Hkv, S_cap, d = 3, 4, 2, 50, 32
+    q = bits(rng.standard_normal((B, H, d)))
+    K = bits(rng.standard_normal((B, Hkv, S_cap, d)))
+    V = bits(rng.standard_normal((B, Hkv, S_cap, d)))
+    lens = np.array([50, 1, 17], np.int32)
+    out = oracle.full_attention(q, K, V, F16, lens, nthreads=2)
+    K2, V2 = K.copy(), V.copy()
+    for b in range(B):
+        K2[b, :, lens[b]:] = bits(rng.standard_normal((Hkv, S_cap - lens[b], d)) * 50)
+        V2[b, :, lens[b]:] = 0x7C00  # +inf bit pattern beyond the length
+    out2 = oracle.full_attention(q, K2, V2, F16, lens)
+    assert np.array_equal(out, out2)
+    for b in range(B):
+        for h in range(H):
+            hk = h // (H // Hkv)
+            ref = oracle.full_unit(q[b, h], K[b, hk, :lens[b]], V[b, hk, :lens[b]], F16)
+            assert np.array_equal(out[b, h], ref)
+    with pytest.raises(ValueError):
+        oracle.full_attention(q, K, V, F16, np.array([51, 1, 1], np.int32))
