@@ -48,6 +48,15 @@ def parse():
     ap.add_argument("--prefill", action="store_true",
                     help="also time kcache_prefill_store of one layer's whole context (K to HBM, "
                          "V device-to-host), reported under \"prefill_store\"")
+    ap.add_argument("--hbm-layers", type=int, default=0,
+                    help="the first L layers keep their V cache in HBM and run conventional "
+                         "attention (the method's second knob, section 3.1 / Table 2); -1 = every "
+                         "layer, i.e. the conventional KV-cache baseline")
+    ap.add_argument("--crossover", action="store_true",
+                    help="also time, on one layer of this workload's shape, the KCache launch "
+                         "against conventional attention with V in HBM over a grid of context "
+                         "lengths and N (section 3.2, equations (3)-(4)), reported under "
+                         "\"crossover\"")
     return ap.parse_args()
 
 
@@ -65,6 +74,7 @@ def main():
 
     wl = ki.config(a.config)
     L = a.layers if a.layers > 0 else wl.L
+    Lh = L if a.hbm_layers < 0 else min(a.hbm_layers, L)   # layers with V in HBM
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     ctx = kc.Context(0, kc.workspace_bytes(wl.B, wl.H, wl.S_cap, wl.N))
@@ -86,10 +96,13 @@ def main():
     # one pinned allocation for every layer's V (torch rounds each pinned request up to a
     # power of two: per-layer requests of 1.25 GiB would pin 2 GiB each)
     layer_elems = int(np.prod(shape))
-    v_all = torch.empty(L * layer_elems, dtype=dt, pin_memory=True)
+    v_all = torch.empty(max(L - Lh, 1) * layer_elems, dtype=dt, pin_memory=True)
     for layer in range(L):
         k_cache = torch.empty(shape, dtype=dt, device=dev)
-        v_cache = v_all[layer * layer_elems:(layer + 1) * layer_elems].view(shape)
+        if layer < Lh:
+            v_cache = torch.empty(shape, dtype=dt, device=dev)
+        else:
+            v_cache = v_all[(layer - Lh) * layer_elems:(layer - Lh + 1) * layer_elems].view(shape)
         cache = kc.LayerCache(k_cache, v_cache)
         kt = torch.empty((wl.B, 1, wl.Hkv, wl.d), dtype=dt, device=dev)
         vt = torch.empty((wl.B, 1, wl.Hkv, wl.d), dtype=dt, device=dev)
@@ -123,8 +136,11 @@ def main():
     def step():
         for l in range(L):
             ctx.prefill_store(caches[l], k_tok[l], v_tok[l], pos_last)
-            ctx.decode_attention(caches[l], qs[l], lens_dev, wl.N, out=outs[l], idx_out=idxs[l],
-                                 w_out=ws[l], gather_mode=mode)
+            if l < Lh:
+                ctx.full_attention(caches[l], qs[l], lens_dev, out=outs[l])
+            else:
+                ctx.decode_attention(caches[l], qs[l], lens_dev, wl.N, out=outs[l],
+                                     idx_out=idxs[l], w_out=ws[l], gather_mode=mode)
 
     def timed(n):
         torch.cuda.synchronize()
@@ -152,20 +168,24 @@ def main():
     k_bytes_layer = int(lens.astype(np.int64).sum()) * wl.Hkv * wl.d * 2
     n_eff = np.minimum(lens, wl.N).astype(np.int64)
     v_bytes_layer = int(n_eff.sum()) * wl.H * wl.d * 2
-    fused_path = prof["fused"][1] > 0
+    fused_path = prof["fused"][1] > 0 or Lh == L
     scan_ms, scan_n = prof["fused"] if fused_path else prof["kscan"]
+    full_ms, full_n = prof["full"]
     gat_ms, gat_n = prof["fused"] if fused_path else prof["gather"]
     sel_ms, sel_n = prof["select"]
-    scan_gbps = k_bytes_layer * L * a.steps / (scan_ms * 1e-3) / 1e9 if scan_ms else 0.0
-    gather_gbps = v_bytes_layer * L * a.steps / (gat_ms * 1e-3) / 1e9 if gat_ms else 0.0
+    Lk = L - Lh                       # layers on the KCache path
+    scan_gbps = k_bytes_layer * Lk * a.steps / (scan_ms * 1e-3) / 1e9 if scan_ms else 0.0
+    gather_gbps = v_bytes_layer * Lk * a.steps / (gat_ms * 1e-3) / 1e9 if gat_ms else 0.0
+    full_gbps = 2 * k_bytes_layer * Lh * a.steps / (full_ms * 1e-3) / 1e9 if full_ms else 0.0
 
     # ---- measured denominators
     probes = {}
     if not a.no_probes:
         kflat = caches[0].k.view(-1)
-        vflat = caches[0].v.view(-1)
-        n1g = min(vflat.numel(), (1 << 30) // 2)
         probes["hbm_stream_read_GBps"] = ctx.probe_read(kflat, iters=5)
+    if not a.no_probes and Lk > 0:
+        vflat = caches[-1].v.view(-1)
+        n1g = min(vflat.numel(), (1 << 30) // 2)
         stage = torch.empty(n1g, dtype=dt, device=dev)
         pinned = torch.empty(n1g, dtype=dt, pin_memory=True)
         probes["h2d_pinned_copy_GBps"] = ctx.probe_copy(stage, vflat[:n1g], iters=5)
@@ -179,14 +199,30 @@ def main():
     traffic = None
     try:
         tj = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
-        ent = tj.get("%s/%s" % (wl.name, "fused" if fused_path else "unfused"))
-        if ent and L == wl.L:
+        path = "conventional" if Lh == L else "fused" if fused_path else "unfused"
+        ent = tj.get("%s/%s" % (wl.name, path))
+        if ent and L == wl.L and Lh in (0, L):
             traffic = ent["fetch_bytes_per_launch"] + ent["write_bytes_per_launch"]
     except (OSError, ValueError, KeyError):
         traffic = None
 
+    if Lh == L:   # the conventional baseline: the dominant kernel is the K + V stream
+        roofline = {"bound": "hbm", "kernel": "full_kernel", "achieved": full_gbps,
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": full_gbps / HBM_PEAK_GBPS,
+                    "traffic": traffic, "bytes_per_launch": 2.0 * k_bytes_layer,
+                    "avg_launch_ms": full_ms / max(full_n, 1), "launches": full_n}
+    else:
+        roofline = {
+            "bound": "hbm", "kernel": "fused_kernel" if fused_path else "kscan_kernel",
+            "achieved": scan_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": scan_gbps / HBM_PEAK_GBPS,
+            "traffic": traffic,
+            "bytes_per_launch": k_bytes_layer * Lk * a.steps / max(scan_n, 1),
+            "avg_launch_ms": scan_ms / max(scan_n, 1), "launches": scan_n,
+        }
     result = {
-        "metric": "KCache decode-attn tokens/s",
+        "metric": "KCache decode-attn tokens/s" if Lh < L else
+                  "conventional KV-cache decode-attn tokens/s",
         "value": wl.B / sec_per_step,
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -201,38 +237,37 @@ def main():
         "config": {"workload": wl.name, "layers": L, "batch": wl.B, "q_heads": wl.H,
                    "kv_heads": wl.Hkv, "head_dim": wl.d, "context": int(lens.max()), "top_n": wl.N,
                    "gather": a.gather, "path": "fused" if fused_path else "unfused",
-                   "pipeline_parts": a.parts,
+                   "pipeline_parts": a.parts, "v_in_hbm_layers": Lh,
                    "k_cache_GiB": L * np.prod(shape) * 2 / 2 ** 30, "setup_s": round(setup_s, 1)},
-        "roofline": {
-            "bound": "hbm", "kernel": "fused_kernel" if fused_path else "kscan_kernel",
-            "achieved": scan_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": scan_gbps / HBM_PEAK_GBPS,
-            "traffic": traffic,
-            "bytes_per_launch": k_bytes_layer * L * a.steps / max(scan_n, 1),
-            "avg_launch_ms": scan_ms / max(scan_n, 1), "launches": scan_n,
-        },
+        "roofline": roofline,
         "v_gather": {
             "kernel": "fused_kernel (whole launch)" if fused_path else "gather_kernel",
-            "achieved": gather_gbps, "unit": "GB/s", "bytes_per_step": v_bytes_layer * L,
+            "achieved": gather_gbps, "unit": "GB/s", "bytes_per_step": v_bytes_layer * Lk,
             "avg_launch_ms": gat_ms / max(gat_n, 1), "launches": gat_n,
             "peak_measured_h2d": probes.get("h2d_pinned_copy_GBps"),
             "frac_of_measured": (gather_gbps / probes["h2d_pinned_copy_GBps"]
                                  if probes.get("h2d_pinned_copy_GBps") else None),
-            "link_busy_frac_of_step": (v_bytes_layer * L / sec_per_step / 1e9 /
+            "link_busy_frac_of_step": (v_bytes_layer * Lk / sec_per_step / 1e9 /
                                        probes["h2d_pinned_copy_GBps"]
                                        if probes.get("h2d_pinned_copy_GBps") else None),
         },
         "select": {"avg_launch_ms": sel_ms / max(sel_n, 1), "launches": sel_n},
         "ms_per_step_with_event_profiling": sec_per_step_prof * 1e3,
-        "k_scan_GBps_of_step": k_bytes_layer * L / sec_per_step / 1e9,
+        "hbm_GBps_of_step": k_bytes_layer * (Lk + 2 * Lh) / sec_per_step / 1e9,
+        "full_attention": {"layers": Lh, "kernel": "full_kernel", "achieved": full_gbps,
+                           "unit": "GB/s", "bytes_per_launch": 2.0 * k_bytes_layer,
+                           "avg_launch_ms": full_ms / max(full_n, 1), "launches": full_n},
         "probes": probes,
     }
 
     if a.prefill:
         result["prefill_store"] = prefill_leg(ctx, kc, wl, caches[0], dev, dt)
 
+    if a.crossover and Lk > 0:
+        result["crossover"] = crossover_leg(ctx, kc, wl, caches[-1], qs[-1], dev, probes)
+
     if not a.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, L, a.cpu_units, a.cpu_passes, outs, idxs, ws)
+        result["cpu_baseline"] = cpu_baseline(wl, L, Lh, a.cpu_units, a.cpu_passes, outs, idxs, ws)
     print(json.dumps(result))
 
 
@@ -267,7 +302,63 @@ def prefill_leg(ctx, kc, wl, cache, dev, dt, reps=3):
                     "writes from the store kernel into the mapped host cache"}
 
 
-def cpu_baseline(wl, L, n_units, passes, outs, idxs, ws):
+def crossover_leg(ctx, kc, wl, cache, q, dev, probes, reps=10):
+    """Break-even of section 3.2: the KCache launch (K from HBM, N rows of V over the host
+    link) against conventional attention (K and V from HBM) on one layer of this workload's
+    shape, every sequence at length s, for a grid of s and N.  Times are HIP-event averages
+    per launch.  Equation (4) predicts KCache to be no slower once s/N exceeds
+    BW_HBM / BW_H2D when the two transfers follow each other; a launch that overlaps them
+    breaks even at half that ratio."""
+    hbm_layer = kc.LayerCache(cache.k, cache.v.to(dev))
+    B, H = wl.B, wl.H
+    s_grid = [s for s in (1024, 1536, 2048, 3072, 4096, 6144, 8192, 12288, 16384, 24576, 32768,
+                          49152, 65536) if s <= wl.S_cap]
+    n_grid = [32, 64, 128, 256, 512, 1024]
+    out = torch.empty((B, H, wl.d), dtype=torch.float32, device=dev)
+    rows = []
+    ctx.set_profile(True)
+    for s in s_grid:
+        lens_dev = torch.full((B,), s, dtype=torch.int32, device=dev)
+        ctx.full_attention(hbm_layer, q, lens_dev, out=out)      # warm-up
+        ctx.profile_reset()
+        for _ in range(reps):
+            ctx.full_attention(hbm_layer, q, lens_dev, out=out)
+        ms, n = ctx.profile_read("full")
+        t_full = ms / n * 1e3
+        k_bytes = B * wl.Hkv * s * wl.d * 2
+        row = {"s": s, "full_us": round(t_full, 1),
+               "full_GBps": round(2 * k_bytes / (t_full * 1e-6) / 1e9, 1), "kcache_us": {}}
+        for N in n_grid:
+            if N > s:
+                continue
+            ctx.decode_attention(cache, q, lens_dev, N, out=out)  # warm-up (workspace growth)
+            ctx.profile_reset()
+            for _ in range(reps):
+                ctx.decode_attention(cache, q, lens_dev, N, out=out)
+            ms, n = ctx.profile_read("fused")
+            row["kcache_us"][str(N)] = round(ms / n * 1e3, 1)
+        rows.append(row)
+    ctx.set_profile(False)
+    ctx.device_check()
+    # per N: the ratio s/N at which the two times cross (linear interpolation in s between
+    # the neighbouring grid points; None when they do not cross inside the grid)
+    wins = {}
+    for N in n_grid:
+        pts = [(r["s"], r["kcache_us"][str(N)] - r["full_us"]) for r in rows
+               if str(N) in r["kcache_us"]]
+        wins[str(N)] = None
+        for (s0, d0), (s1, d1) in zip(pts, pts[1:]):
+            if d0 > 0 >= d1:
+                wins[str(N)] = round((s0 + (s1 - s0) * d0 / (d0 - d1)) / N, 1)
+                break
+    hbm, link = probes.get("hbm_stream_read_GBps"), probes.get("zerocopy_row_read_GBps")
+    return {"shape": {"B": B, "H": H, "Hkv": wl.Hkv, "dtype": wl.dtype}, "grid": rows,
+            "break_even_s_over_N": wins,
+            "eq4_ratio_measured_bandwidths": (hbm / link) if hbm and link else None,
+            "eq4_ratio_with_overlap": (hbm / link / 2) if hbm and link else None}
+
+
+def cpu_baseline(wl, L, Lh, n_units, passes, outs, idxs, ws):
     """The CPU oracle, as it stands, on a seeded sample of this workload's units,
     one thread per available core; its results double as a spot check of the GPU
     outputs of the last timed step."""
@@ -303,6 +394,15 @@ def cpu_baseline(wl, L, n_units, passes, outs, idxs, ws):
     checked = identical = 0
     failures = []
     for i, (l, b, h) in enumerate(picks[:16]):
+        if l < Lh:   # a layer with V in HBM ran conventional attention
+            ref = oracle.full_unit(q[i, 0], K[i, 0, :sl[i]], V[i, 0, :sl[i]], code)
+            err = np.abs(outs[l][b, h].cpu().numpy().astype(np.float64) - ref)
+            if (err <= 1e-3 + 2e-3 * np.abs(ref)).all():
+                checked += 1
+                identical += 1
+            else:
+                failures.append("%s: conventional attention max err %g" % ((l, b, h), err.max()))
+            continue
         r = oracle.decode_unit(q[i, 0], K[i, 0, :sl[i]], V[i, 0, :sl[i]], code, wl.N,
                                want_scores=True)
         r["v"] = oracle.decode16(V[i, 0, :sl[i]], code)

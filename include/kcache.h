@@ -48,7 +48,8 @@ typedef enum {
   KC_OK = 0,
   KC_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, H % Hkv != 0 ...     */
   KC_ERR_UNSUPPORTED = -2, /* head_dim other than 128, group size not in {1,2,4,8}  */
-  KC_ERR_NOT_PINNED = -3,  /* v_host is not device-mapped host memory                */
+  KC_ERR_NOT_PINNED = -3,  /* v_host is not device-mapped host memory (or, with
+                              v_in_hbm, not device memory)                           */
   KC_ERR_WORKSPACE = -4,   /* workspace could not be (re)allocated                   */
   KC_ERR_HIP = -5,         /* a HIP runtime call failed; see kcache_last_error       */
   KC_ERR_DEVICE_CHECK = -6 /* a kernel found pos / seq_lens outside the cache        */
@@ -59,13 +60,17 @@ typedef enum {
  * the K rows of one (sequence, KV head) form one contiguous stream and every V
  * row is one contiguous 256-byte read (section 3.1: K in HBM, V in CPU memory). */
 typedef struct {
-  void* k_dev;    /* dev   [B][Hkv][S_cap][d], 16-bit elements                       */
-  void* v_host;   /* host  [B][Hkv][S_cap][d], same layout, pinned + mapped          */
-  int32_t B;      /* sequences                                                       */
-  int32_t Hkv;    /* KV heads                                                        */
-  int32_t S_cap;  /* capacity in positions                                           */
-  int32_t d;      /* head dimension d_h; must be 128                                 */
-  int32_t dtype;  /* kc_dtype of q, K, V                                             */
+  void* k_dev;      /* dev   [B][Hkv][S_cap][d], 16-bit elements                     */
+  void* v_host;     /* host  [B][Hkv][S_cap][d], same layout, pinned + mapped; with
+                       v_in_hbm != 0 a dev pointer of the same layout instead        */
+  int32_t B;        /* sequences                                                     */
+  int32_t Hkv;      /* KV heads                                                      */
+  int32_t S_cap;    /* capacity in positions                                         */
+  int32_t d;        /* head dimension d_h; must be 128                               */
+  int32_t dtype;    /* kc_dtype of q, K, V                                           */
+  int32_t v_in_hbm; /* 0: V in CPU memory (the method's default placement);
+                       1: this layer keeps its V cache in HBM (section 3.1 and the
+                       caption of Table 2: the first L layers)                      */
 } kc_layer_cache;
 
 /* Identifiers for kcache_profile_read. */
@@ -76,7 +81,8 @@ typedef enum {
   KC_KERNEL_STORE_K = 3, /* cache store, K half                                      */
   KC_KERNEL_STORE_V = 4, /* cache store, V half (device to host)                     */
   KC_KERNEL_FUSED = 5,   /* scan + select + V pull + weighted sum in one launch      */
-  KC_KERNEL_COUNT = 6
+  KC_KERNEL_FULL = 6,    /* conventional attention, K and V in HBM                   */
+  KC_KERNEL_COUNT = 7
 } kc_kernel_id;
 
 /* Integer options for kcache_set_option. */
@@ -134,7 +140,8 @@ int kcache_check_shapes(const kc_layer_cache* cache, int32_t H, int32_t N);
  * cache->v_host by a kernel on an internal side stream ordered after `stream`;
  * later kcache_decode_attention calls on the same context wait for it on the
  * device.  The caller must keep v_new_dev alive until done_event (or a
- * kcache_synchronize) has completed.
+ * kcache_synchronize) has completed.  With cache->v_in_hbm both halves are
+ * written on `stream` by one launch.
  */
 int kcache_prefill_store(kc_ctx* ctx, const kc_layer_cache* cache, const void* k_new_dev,
                          const void* v_new_dev, const int32_t* pos_dev, int32_t T, void* stream,
@@ -160,11 +167,27 @@ int kcache_prefill_store(kc_ctx* ctx, const kc_layer_cache* cache, const void* k
  *   gather_mode   kc_gather_mode
  *   stream        hipStream_t; all results are complete in stream order
  * Scores and softmax are fp32; the selection is made on the fp32 scores.
+ * A layer with cache->v_in_hbm is accepted too (its N rows then come from HBM);
+ * KC_GATHER_STAGED is KC_ERR_UNSUPPORTED for such a layer.
  */
 int kcache_decode_attention(kc_ctx* ctx, const kc_layer_cache* cache, const void* q_dev, int32_t H,
                             const int32_t* seq_lens_dev, int32_t N, float* out_dev,
                             int32_t* idx_out_dev, float* w_out_dev, int32_t gather_mode,
                             void* stream);
+
+/*
+ * Conventional decode attention for one layer whose V cache is in HBM
+ * (cache->v_in_hbm == 1):  out = softmax(q K^T / sqrt(d_h)) V over all s_b cached
+ * positions (section 2; Table 1, rows S and A of plain MHA).  This is what the
+ * layers that keep V in HBM run (section 3.1; Table 2 caption) and the baseline
+ * of the break-even analysis (section 3.2, equations (3)-(4)).
+ *   q_dev, H, seq_lens_dev, stream   as for kcache_decode_attention
+ *   out_dev                          dev fp32 [B][H][d]
+ * Scores, softmax and accumulation are fp32.  Returns KC_ERR_INVALID_ARG when the
+ * layer's V cache is not in HBM.
+ */
+int kcache_full_attention(kc_ctx* ctx, const kc_layer_cache* cache, const void* q_dev, int32_t H,
+                          const int32_t* seq_lens_dev, float* out_dev, void* stream);
 
 /* Block until everything this context has enqueued (side streams included) is done. */
 int kcache_synchronize(kc_ctx* ctx);

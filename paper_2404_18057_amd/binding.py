@@ -11,7 +11,8 @@ _HEADER = os.path.join(os.path.dirname(_HERE), "include", "kcache.h")
 
 KC_F16, KC_BF16 = 0, 1
 GATHER_ZEROCOPY, GATHER_STAGED = 0, 1
-KERNELS = {"kscan": 0, "select": 1, "gather": 2, "store_k": 3, "store_v": 4, "fused": 5}
+KERNELS = {"kscan": 0, "select": 1, "gather": 2, "store_k": 3, "store_v": 4, "fused": 5,
+           "full": 6}
 OPT_PIPELINE_PARTS, OPT_PROFILE, OPT_STAGED_THREADS, OPT_FUSED, OPT_FUSED_ROWS = 0, 1, 2, 3, 4
 
 _c_i32, _c_i64, _c_p, _c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
@@ -25,7 +26,7 @@ class KCacheError(RuntimeError):
 
 class _CLayerCache(ctypes.Structure):
     _fields_ = [("k_dev", _c_p), ("v_host", _c_p), ("B", _c_i32), ("Hkv", _c_i32),
-                ("S_cap", _c_i32), ("d", _c_i32), ("dtype", _c_i32)]
+                ("S_cap", _c_i32), ("d", _c_i32), ("dtype", _c_i32), ("v_in_hbm", _c_i32)]
 
 
 _lib = None
@@ -59,6 +60,7 @@ def lib():
                                                     _c_p]),
             "kcache_decode_attention": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_i32, _c_p, _c_i32,
                                                        _c_p, _c_p, _c_p, _c_i32, _c_p]),
+            "kcache_full_attention": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_i32, _c_p, _c_p, _c_p]),
             "kcache_synchronize": (ctypes.c_int, [_c_p]),
             "kcache_device_check": (ctypes.c_int, [_c_p]),
             "kcache_profile_read": (ctypes.c_int, [_c_p, _c_i32, dbl_p, i64_p]),
@@ -90,20 +92,22 @@ def workspace_bytes(B, H, S_cap, N):
 
 
 class LayerCache:
-    """One layer's K cache (device tensor) and V cache (pinned host tensor),
-    both [B][Hkv][S_cap][d] in fp16 or bf16.  Holds references, owns nothing else."""
+    """One layer's K cache (device tensor) and V cache, both [B][Hkv][S_cap][d] in
+    fp16 or bf16.  The V cache is a pinned host tensor, or a device tensor for a
+    layer that keeps V in HBM.  Holds references, owns nothing else."""
 
-    def __init__(self, k_dev, v_host):
-        if k_dev.dtype != v_host.dtype or k_dev.shape != v_host.shape or k_dev.dim() != 4:
+    def __init__(self, k_dev, v):
+        if k_dev.dtype != v.dtype or k_dev.shape != v.shape or k_dev.dim() != 4:
             raise ValueError("K and V caches must have the same 4-d shape and dtype")
-        if not (k_dev.is_contiguous() and v_host.is_contiguous()):
+        if not (k_dev.is_contiguous() and v.is_contiguous()):
             raise ValueError("caches must be contiguous")
-        if not k_dev.is_cuda or v_host.is_cuda:
-            raise ValueError("K cache must be a device tensor, V cache a host tensor")
-        self.k, self.v = k_dev, v_host
+        if not k_dev.is_cuda:
+            raise ValueError("K cache must be a device tensor")
+        self.k, self.v = k_dev, v
+        self.v_in_hbm = bool(v.is_cuda)
         B, Hkv, S_cap, d = k_dev.shape
-        self.c = _CLayerCache(k_dev.data_ptr(), v_host.data_ptr(), B, Hkv, S_cap, d,
-                              _dtype_code(k_dev.dtype))
+        self.c = _CLayerCache(k_dev.data_ptr(), v.data_ptr(), B, Hkv, S_cap, d,
+                              _dtype_code(k_dev.dtype), 1 if self.v_in_hbm else 0)
 
 
 def _dtype_code(dt):
@@ -116,7 +120,7 @@ def _dtype_code(dt):
 
 def check_shapes(B, Hkv, S_cap, d, dtype_code, H, N):
     """Host-only shape validation (no GPU needed); returns the kc_status."""
-    c = _CLayerCache(None, None, B, Hkv, S_cap, d, dtype_code)
+    c = _CLayerCache(None, None, B, Hkv, S_cap, d, dtype_code, 0)
     return int(lib().kcache_check_shapes(ctypes.byref(c), H, N))
 
 
@@ -182,7 +186,13 @@ class Context:
             raise ValueError("inputs must be contiguous")
         if pos.dtype != torch.int32 or pos.numel() != B or not pos.is_cuda:
             raise ValueError("pos must be a device int32 [B] tensor")
-        ev = ctypes.c_void_p(done_event.cuda_event) if done_event is not None else None
+        ev = None
+        if done_event is not None:
+            if not done_event.cuda_event:
+                # torch creates the HIP event lazily at its first record(); without a handle
+                # the library would record nothing and a later synchronize() would not wait
+                done_event.record(torch.cuda.current_stream() if stream is None else stream)
+            ev = ctypes.c_void_p(done_event.cuda_event)
         self._check(lib().kcache_prefill_store(self._h, ctypes.byref(cache.c), _ptr(k_new),
                                                _ptr(v_new), _ptr(pos), T, _stream_ptr(stream), ev))
 
@@ -207,6 +217,22 @@ class Context:
         self._check(lib().kcache_decode_attention(
             self._h, ctypes.byref(cache.c), _ptr(q), H, _ptr(seq_lens), int(N), _ptr(out),
             _ptr(idx_out), _ptr(w_out), int(gather_mode), _stream_ptr(stream)))
+        return out
+
+    def full_attention(self, cache, q, seq_lens, out=None, stream=None):
+        """Conventional attention of a layer whose V cache is in HBM.  Returns out fp32 [B][H][d]."""
+        B, H, d = q.shape
+        if (B, d) != (cache.c.B, cache.c.d) or q.dtype != cache.k.dtype or not q.is_contiguous():
+            raise ValueError("q does not match the cache")
+        if seq_lens.dtype != torch.int32 or seq_lens.numel() != B or not seq_lens.is_cuda:
+            raise ValueError("seq_lens must be a device int32 [B] tensor")
+        if out is None:
+            out = torch.empty((B, H, d), dtype=torch.float32, device=q.device)
+        if out.dtype != torch.float32 or not out.is_contiguous() or not out.is_cuda or \
+                out.shape != (B, H, d):
+            raise ValueError("out must be a contiguous device fp32 [B][H][d] tensor")
+        self._check(lib().kcache_full_attention(self._h, ctypes.byref(cache.c), _ptr(q), H,
+                                                _ptr(seq_lens), _ptr(out), _stream_ptr(stream)))
         return out
 
     def synchronize(self):

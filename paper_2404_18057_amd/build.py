@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkcache.so")
-SOURCES = ["api.cpp", "kscan.hip", "select.hip", "gather.hip", "decode_fused.hip", "store.hip", "probe.hip"]
+SOURCES = ["api.cpp", "kscan.hip", "select.hip", "gather.hip", "decode_fused.hip", "full_attention.hip", "store.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
          # no compiler-generated packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -296,6 +296,25 @@ int mapped_host_pointer(kc_ctx* c, void* host, void** dev) {
   return KC_OK;
 }
 
+// Device-visible address of a layer's V cache: the mapped host cache, or the
+// device buffer of a layer that keeps V in HBM.
+int v_pointer(kc_ctx* c, const kc_layer_cache* cache, void** dev) {
+  if (!cache->v_in_hbm) return mapped_host_pointer(c, cache->v_host, dev);
+  hipPointerAttribute_t attr;
+  memset(&attr, 0, sizeof attr);
+  hipError_t e = hipPointerGetAttributes(&attr, cache->v_host);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(c, KC_ERR_NOT_PINNED, "V cache %p is not known to HIP (%s): with v_in_hbm it must "
+                "be device memory", cache->v_host, hipGetErrorString(e));
+  }
+  if (attr.type != hipMemoryTypeDevice)
+    return fail(c, KC_ERR_NOT_PINNED, "V cache %p has memory type %d, expected device memory "
+                "(v_in_hbm is set)", cache->v_host, (int)attr.type);
+  *dev = cache->v_host;
+  return KC_OK;
+}
+
 int shape_status(const kc_layer_cache* cache, int32_t H, int32_t N, const char** why) {
   *why = "";
   if (!cache) return *why = "cache is NULL", KC_ERR_INVALID_ARG;
@@ -303,6 +322,8 @@ int shape_status(const kc_layer_cache* cache, int32_t H, int32_t N, const char**
     return *why = "B, Hkv and S_cap must be positive", KC_ERR_INVALID_ARG;
   if (cache->dtype != KC_F16 && cache->dtype != KC_BF16)
     return *why = "dtype must be KC_F16 or KC_BF16", KC_ERR_INVALID_ARG;
+  if (cache->v_in_hbm != 0 && cache->v_in_hbm != 1)
+    return *why = "v_in_hbm must be 0 or 1", KC_ERR_INVALID_ARG;
   if (cache->d != kc::kHeadDim) return *why = "head dimension must be 128", KC_ERR_UNSUPPORTED;
   if ((int64_t)cache->B * cache->Hkv * cache->S_cap >= (1ll << 40))
     return *why = "cache too large", KC_ERR_INVALID_ARG;
@@ -473,10 +494,20 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
   DeviceGuard g(c->device);
   if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
   void* v_map = nullptr;
-  if ((rc = mapped_host_pointer(c, cache->v_host, &v_map)) != KC_OK) return rc;
+  if ((rc = v_pointer(c, cache, &v_map)) != KC_OK) return rc;
 
   hipStream_t st = (hipStream_t)stream;
   const kc::Shape sh{cache->B, 0, cache->Hkv, cache->S_cap, 0, cache->dtype};
+  if (cache->v_in_hbm) {
+    // both caches in HBM: one launch over the whole grid on the caller's stream
+    {
+      KernelTimer t(c, KC_KERNEL_STORE_K, st);
+      KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, v_new_dev, v_map, pos_dev, T,
+                                 c->flags, 0, st));
+    }
+    if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, st));
+    return KC_OK;
+  }
   if ((int64_t)cache->B * T * cache->Hkv <= 4096) {
     // a decode-step append: K and V rows in one small launch on the caller's stream
     // (too little data to be worth a second stream and two event waits)
@@ -522,8 +553,11 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
                 gather_mode);
   DeviceGuard g(c->device);
   if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  if (cache->v_in_hbm && gather_mode == KC_GATHER_STAGED)
+    return fail(c, KC_ERR_UNSUPPORTED, "kcache_decode_attention: the staged gather needs the V "
+                "cache in host memory");
   void* v_map = nullptr;
-  if ((rc = mapped_host_pointer(c, cache->v_host, &v_map)) != KC_OK) return rc;
+  if ((rc = v_pointer(c, cache, &v_map)) != KC_OK) return rc;
 
   const int B = cache->B, Hkv = cache->Hkv, S_cap = cache->S_cap, G = H / Hkv;
   const size_t units = (size_t)B * H;
@@ -687,6 +721,66 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
     }
     KC_HIP(c, hipEventRecord(c->ev_join, c->side));
     KC_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
+  }
+  KC_HIP(c, hipEventRecord(c->ev_last, st));
+  c->have_last = true;
+  return KC_OK;
+}
+
+int kcache_full_attention(kc_ctx* c, const kc_layer_cache* cache, const void* q_dev, int32_t H,
+                          const int32_t* seq_lens_dev, float* out_dev, void* stream) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  const char* why;
+  int rc = shape_status(cache, H == 0 ? -1 : H, 1, &why);
+  if (rc != KC_OK) return fail(c, rc, "kcache_full_attention: %s", why);
+  if (!cache->k_dev || !cache->v_host || !q_dev || !seq_lens_dev || !out_dev)
+    return fail(c, KC_ERR_INVALID_ARG, "kcache_full_attention: NULL pointer argument");
+  if (!cache->v_in_hbm)
+    return fail(c, KC_ERR_INVALID_ARG, "kcache_full_attention: this layer's V cache is in host "
+                "memory (v_in_hbm is 0); use kcache_decode_attention");
+  DeviceGuard g(c->device);
+  if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  void* v_map = nullptr;
+  if ((rc = v_pointer(c, cache, &v_map)) != KC_OK) return rc;
+
+  const int B = cache->B, Hkv = cache->Hkv, S_cap = cache->S_cap, G = H / Hkv;
+  const size_t units = (size_t)B * H;
+  const int kv_units = B * Hkv;
+  const int R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
+                    ? c->fused_rows
+                    : kc::full_rows_per_block(kv_units, G, S_cap);
+  const int chunks_cap = (S_cap + R - 1) / R;
+  const size_t part_bytes = round256(units * chunks_cap * sizeof(float2));
+  const size_t need = part_bytes + round256(units * chunks_cap * kc::kHeadDim * sizeof(float));
+  if ((rc = ensure_workspace(c, need)) != KC_OK) return rc;
+  if ((rc = ensure_counters(c, kv_units)) != KC_OK) return rc;
+
+  hipStream_t st = (hipStream_t)stream;
+  if (c->have_last) KC_HIP(c, hipStreamWaitEvent(st, c->ev_last, 0));
+  if (c->store_pending) {
+    KC_HIP(c, hipStreamWaitEvent(st, c->ev_store, 0));
+    c->store_pending = false;
+  }
+  kc::FullArgs a;
+  a.q = static_cast<const uint16_t*>(q_dev);
+  a.K = static_cast<const uint16_t*>(cache->k_dev);
+  a.V = static_cast<const uint16_t*>(v_map);
+  a.seq_lens = seq_lens_dev;
+  a.out = out_dev;
+  a.part = reinterpret_cast<float2*>(c->ws);
+  a.part_o = reinterpret_cast<float*>(static_cast<char*>(c->ws) + part_bytes);
+  a.counters = c->counters;
+  a.flags = c->flags;
+  a.H = H;
+  a.Hkv = Hkv;
+  a.S_cap = S_cap;
+  a.R = R;
+  a.chunks_cap = chunks_cap;
+  a.kv_count = kv_units;
+  a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
+  {
+    KernelTimer t(c, KC_KERNEL_FULL, st);
+    KC_HIP(c, kc::launch_full(a, cache->dtype, st));
   }
   KC_HIP(c, hipEventRecord(c->ev_last, st));
   c->have_last = true;

@@ -1,0 +1,139 @@
+// Device helpers shared by the attention kernels of this library: the 256-byte
+// row layout (16 lanes x 16 bytes), dot products and row reductions, the K scan
+// of one chunk into LDS, and the cache-bypassing loads / stores used to hand
+// data from one workgroup to another inside a launch.
+#pragma once
+
+#include "kc_internal.h"
+
+namespace kc {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf162_t __attribute__((ext_vector_type(2)));
+
+template <int DT>
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
+  if constexpr (DT == 0) {
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b),
+                                  acc, false);
+  } else {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf162_t, a),
+                                           __builtin_bit_cast(bf162_t, b), acc, false);
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ float dot8(const uint4& k, const uint4& q) {
+  float a = dot2<DT>(k.x, q.x, 0.f);
+  a = dot2<DT>(k.y, q.y, a);
+  a = dot2<DT>(k.z, q.z, a);
+  return dot2<DT>(k.w, q.w, a);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true);
+  return x + __builtin_bit_cast(float, y);
+}
+
+// Sum over the 16 lanes of a DPP row, returned to every lane of the row.
+__device__ __forceinline__ float row16_sum(float x) {
+  x = dpp_add<0xB1>(x);   // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);   // quad_perm [2,3,0,1]
+  x = dpp_add<0x141>(x);  // row_half_mirror
+  x = dpp_add<0x140>(x);  // row_mirror
+  return x;
+}
+
+// acc[0..7] += w * (the 8 16-bit values of v)
+template <int DT>
+__device__ __forceinline__ void fma8(float (&acc)[8], const uint4& v, float w) {
+  const uint32_t r[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float lo, hi;
+    if constexpr (DT == 0) {
+      half2_t h = __builtin_bit_cast(half2_t, r[i]);
+      lo = (float)h.x;
+      hi = (float)h.y;
+    } else {
+      lo = __uint_as_float(r[i] << 16);
+      hi = __uint_as_float(r[i] & 0xffff0000u);
+    }
+    acc[2 * i] = fmaf(w, lo, acc[2 * i]);
+    acc[2 * i + 1] = fmaf(w, hi, acc[2 * i + 1]);
+  }
+}
+
+// Data that one workgroup hands to another inside the launch (chunk candidates
+// and partials) is written through to memory and read around the per-XCD L2 with
+// device-scope relaxed atomics (sc1 stores / loads).  That keeps the hand-over
+// coherent across XCDs without the L2 write-back / invalidate walk that a
+// release / acquire fence costs (about 1 us each, thousands per launch).
+template <typename T>
+__device__ __forceinline__ void st_dev(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ T ld_dev(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Scores of the R positions [row0, row0 + R) of one (sequence, KV head) against
+// the G query heads of its group, written to z[g * R + local] (LDS); local is the
+// position relative to row0.  Called by all NT threads of the workgroup.
+//
+// A K row is 16 lanes x 16 bytes, so a wave-wide 16-byte load reads 4 rows as one
+// coalesced 1 KiB request; 16 such loads are issued back to back (16 KiB per wave
+// in flight) with the non-temporal hint.  Each lane multiplies its 8 values with
+// q (fp32 accumulate); the 16 partials of a row are added inside the DPP row.
+// Rows at or beyond s are not loaded past S_cap and their scores are not defined.
+template <int DT, int G, int NT>
+__device__ __forceinline__ void score_chunk(const uint16_t* __restrict__ q_group,
+                                            const uint16_t* __restrict__ K_unit, int S_cap, int s,
+                                            int row0, int R, float scale, float* z) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane & 15, rg = lane >> 4;
+  uint4 qv[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    qv[g] = *reinterpret_cast<const uint4*>(q_group + (size_t)g * kHeadDim + sub * 8);
+  const uint4* __restrict__ Kp = reinterpret_cast<const uint4*>(K_unit);
+  const int rows_per_wave = R / (NT / 64);  // a multiple of 64
+#pragma unroll 1
+  for (int it = 0; it < rows_per_wave / 64; ++it) {
+    const int local = wave * rows_per_wave + it * 64;
+    const int base = row0 + local;
+    if (base >= s) break;
+    uint4 kr[16];
+    if (base + 64 <= S_cap) {
+      const uint4* p = Kp + (size_t)(base + rg) * 16 + sub;
+#pragma unroll
+      for (int u = 0; u < 16; ++u) kr[u] = load_stream16(p + u * 64);
+    } else {  // last rows of the cache: never read beyond S_cap
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        int r = base + u * 4 + rg;
+        r = r < S_cap ? r : S_cap - 1;
+        kr[u] = Kp[(size_t)r * 16 + sub];
+      }
+    }
+    float keep[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) keep[g] = 0.f;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float x = row16_sum(dot8<DT>(kr[u], qv[g]));
+        keep[g] = (sub == u) ? x : keep[g];
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) z[g * R + local + sub * 4 + rg] = keep[g] * scale;
+  }
+}
+
+constexpr int kXcds = 8;  // accelerator complex dies of an MI355X
+
+}  // namespace kc

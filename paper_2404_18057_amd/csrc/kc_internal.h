@@ -78,6 +78,26 @@ struct FusedArgs {
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N);
 hipError_t launch_fused(const FusedArgs& a, int dtype, int kv_count, hipStream_t st);
 
+// Conventional attention with K and V in HBM (full_attention.hip).
+struct FullArgs {
+  const uint16_t* q;
+  const uint16_t* K;
+  const uint16_t* V;  // device-visible [B][Hkv][S_cap][d]
+  const int32_t* seq_lens;
+  float* out;
+  float2* part;   // [units][chunks_cap] (max, sum of exp(z - max)) of each chunk
+  float* part_o;  // [units][chunks_cap][d] sum of exp(z - max) * V over the chunk
+  int* counters;  // [kv units] arrival tickets, zero between launches
+  int* flags;
+  int H, Hkv, S_cap;
+  int R;           // positions per workgroup, a multiple of kFusedThreads, R * G <= kFusedZFloats
+  int chunks_cap;  // ceil(S_cap / R)
+  int kv_count;
+  float scale;
+};
+int full_rows_per_block(int kv_units, int G, int S_cap);
+hipError_t launch_full(const FullArgs& a, int dtype, hipStream_t st);
+
 hipError_t launch_probe_read(const void* ptr, size_t bytes, uint32_t* sink, hipStream_t st);
 hipError_t launch_probe_rows(const void* ptr, size_t total_rows, int64_t n_rows, uint32_t* sink,
                              hipStream_t st);
