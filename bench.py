@@ -5,7 +5,9 @@ A step is one decode step of the whole hot path over one batch: for every
 layer, the new token's K/V rows are stored (T = 1) and kcache_decode_attention
 runs (K scan over the full context, softmax, top-N, V pull from pinned host
 memory, weighted sum).  All inputs are synthetic, seeded, and already resident
-(K in HBM, V in pinned host memory) when the timed region starts.
+(K in HBM, V in pinned host memory) when the timed region starts.  By default the
+step is issued as one launch of a HIP graph captured from kcache_decode_step (the
+same kernels in the same order on one stream); --step-mode selects the eager forms.
 
 Prints one JSON line: tokens/s for the whole job, the HBM roofline of the K-scan
 kernel (HIP events around every launch, taken live in a second timed pass of
@@ -48,6 +50,15 @@ def parse():
     ap.add_argument("--prefill", action="store_true",
                     help="also time kcache_prefill_store of one layer's whole context (K to HBM, "
                          "V device-to-host), reported under \"prefill_store\"")
+    ap.add_argument("--step-mode", choices=["graph", "step", "calls"], default="graph",
+                    help="how a decode step is issued: one captured HIP graph launch (default), "
+                         "one kcache_decode_step call, or per-layer store + attention calls")
+    ap.add_argument("--lanes", type=int, default=1,
+                    help="streams the layers of a step are dealt over (kcache_decode_step); more "
+                         "than 1 lets consecutive layers overlap, which is only meaningful for "
+                         "the attention in isolation")
+    ap.add_argument("--no-overlap-leg", action="store_true",
+                    help="skip the extra timed pass with two lanes reported under layer_overlap")
     ap.add_argument("--hbm-layers", type=int, default=0,
                     help="the first L layers keep their V cache in HBM and run conventional "
                          "attention (the method's second knob, section 3.1 / Table 2); -1 = every "
@@ -133,7 +144,15 @@ def main():
     idxs = [torch.empty((wl.B, wl.H, wl.N), dtype=torch.int32, device=dev) for _ in range(L)]
     ws = [torch.empty((wl.B, wl.H, wl.N), dtype=torch.float32, device=dev) for _ in range(L)]
 
-    def step():
+    step_layers = [dict(cache=caches[l], k_new=k_tok[l], v_new=v_tok[l], q=qs[l], out=outs[l],
+                        idx_out=idxs[l], w_out=ws[l]) for l in range(L)]
+    plain = mode == kc.GATHER_ZEROCOPY and not a.unfused   # what the step calls implement
+    step_mode = a.step_mode if plain else "calls"
+    ctx.set_step_lanes(a.lanes)
+    graph = ctx.step_graph(step_layers, wl.H, pos_last, lens_dev, wl.N) \
+        if step_mode == "graph" else None
+
+    def step_calls():
         for l in range(L):
             ctx.prefill_store(caches[l], k_tok[l], v_tok[l], pos_last)
             if l < Lh:
@@ -141,6 +160,11 @@ def main():
             else:
                 ctx.decode_attention(caches[l], qs[l], lens_dev, wl.N, out=outs[l],
                                      idx_out=idxs[l], w_out=ws[l], gather_mode=mode)
+
+    def step_eager():
+        ctx.decode_step(step_layers, wl.H, pos_last, lens_dev, wl.N)
+
+    step = {"graph": (lambda: graph.launch()), "step": step_eager, "calls": step_calls}[step_mode]
 
     def timed(n):
         torch.cuda.synchronize()
@@ -156,7 +180,33 @@ def main():
         step()
     sec_per_step = timed(a.steps)
 
+    # ---- optional: the same step with the layers dealt over two streams
+    overlap = None
+    if plain and not a.no_overlap_leg and a.lanes == 1 and L > 1:
+        if graph is not None:
+            graph.close()
+        ctx.set_step_lanes(2)
+        g2 = ctx.step_graph(step_layers, wl.H, pos_last, lens_dev, wl.N)
+        ctx.set_step_lanes(1)
+        keep = step
+        step = lambda: g2.launch()
+        for _ in range(a.warmup):
+            step()
+        sec2 = timed(a.steps)
+        g2.close()
+        step = keep
+        overlap = {"lanes": 2, "ms_per_step": sec2 * 1e3, "tokens_per_s": wl.B / sec2,
+                   "note": "consecutive layers on two streams: the K scan of one layer hides the "
+                           "merge / V-pull tail of the one before.  Valid for the attention in "
+                           "isolation only (every layer's q is given up front); not the headline "
+                           "value"}
+        graph = None
+
     # ---- second pass of the same steps with HIP events around every kernel launch
+    # (eager launches: events are not part of a captured graph)
+    if step_mode == "graph":
+        step = step_eager
+    ctx.set_step_lanes(1)   # one launch at a time: its duration is the kernel's own
     ctx.set_profile(True)
     ctx.profile_reset()
     sec_per_step_prof = timed(a.steps)
@@ -187,9 +237,12 @@ def main():
         vflat = caches[-1].v.view(-1)
         n1g = min(vflat.numel(), (1 << 30) // 2)
         stage = torch.empty(n1g, dtype=dt, device=dev)
-        pinned = torch.empty(n1g, dtype=dt, pin_memory=True)
+        # the boxes pin little more than the 64 GiB of V that config 2 needs (a 66th GiB is
+        # refused): the device-to-host probe gets by with a 256 MiB target
+        n256m = min(n1g, (1 << 28) // 2)
+        pinned = torch.empty(n256m, dtype=dt, pin_memory=True)
         probes["h2d_pinned_copy_GBps"] = ctx.probe_copy(stage, vflat[:n1g], iters=5)
-        probes["d2h_pinned_copy_GBps"] = ctx.probe_copy(pinned, stage, iters=5)
+        probes["d2h_pinned_copy_GBps"] = ctx.probe_copy(pinned, stage[:n256m], iters=20)
         probes["zerocopy_stream_read_GBps"] = ctx.probe_read(vflat[:n1g], iters=3)
         probes["zerocopy_row_read_GBps"] = ctx.probe_rows(vflat, 1 << 20, iters=3)
         del stage, pinned
@@ -237,7 +290,8 @@ def main():
         "config": {"workload": wl.name, "layers": L, "batch": wl.B, "q_heads": wl.H,
                    "kv_heads": wl.Hkv, "head_dim": wl.d, "context": int(lens.max()), "top_n": wl.N,
                    "gather": a.gather, "path": "fused" if fused_path else "unfused",
-                   "pipeline_parts": a.parts, "v_in_hbm_layers": Lh,
+                   "pipeline_parts": a.parts, "v_in_hbm_layers": Lh, "step_mode": step_mode,
+                   "lanes": a.lanes,
                    "k_cache_GiB": L * np.prod(shape) * 2 / 2 ** 30, "setup_s": round(setup_s, 1)},
         "roofline": roofline,
         "v_gather": {
@@ -258,6 +312,7 @@ def main():
                            "unit": "GB/s", "bytes_per_launch": 2.0 * k_bytes_layer,
                            "avg_launch_ms": full_ms / max(full_n, 1), "launches": full_n},
         "probes": probes,
+        "layer_overlap": overlap,
     }
 
     if a.prefill:

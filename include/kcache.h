@@ -96,9 +96,17 @@ typedef enum {
   KC_OPT_FUSED = 3,          /* 1 (default): KC_GATHER_ZEROCOPY decodes run as one fused
                                 launch per layer whose scores never leave the chip;
                                 0: separate scan / select / gather launches            */
-  KC_OPT_FUSED_ROWS = 4      /* positions scored per workgroup of the fused launch: a
+  KC_OPT_FUSED_ROWS = 4,     /* positions scored per workgroup of the fused launch: a
                                 multiple of 512 with rows * (H/Hkv) <= 8192, or 0 =
                                 choose from the shape (default)                        */
+  KC_OPT_STEP_LANES = 5      /* kcache_decode_step / kcache_step_graph_create: 1 (default)
+                                runs the layers one after another on the caller's
+                                stream; 2..4 deals them over that many internal streams
+                                so that the K scan of one layer overlaps the tail (merge
+                                and V pull) of the one before.  Only valid when every
+                                layer's q is available up front, as in a benchmark of
+                                the attention alone: in a model, layer l+1's query
+                                depends on layer l's output                            */
 } kc_option;
 
 /* Create a context on `device` (a HIP device ordinal) with a workspace of at
@@ -188,6 +196,49 @@ int kcache_decode_attention(kc_ctx* ctx, const kc_layer_cache* cache, const void
  */
 int kcache_full_attention(kc_ctx* ctx, const kc_layer_cache* cache, const void* q_dev, int32_t H,
                           const int32_t* seq_lens_dev, float* out_dev, void* stream);
+
+/*
+ * A whole decode step in one call (Figure 1: every layer pushes the new token's K
+ * and V states, then attends): for l = 0 .. L-1, in order, append layers[l]'s new
+ * rows (T = 1, as kcache_prefill_store) and run its attention -- KCache top-N
+ * (kcache_decode_attention, zero-copy gather) for a layer whose V cache is in host
+ * memory, conventional attention (kcache_full_attention) for a layer with
+ * v_in_hbm.  Same results as the per-layer calls; saves their host-side overhead
+ * and is the unit that kcache_step_graph_create captures.
+ *   layers        host array of L entries (read during the call only)
+ *   H, N          as for kcache_decode_attention, shared by all layers
+ *   pos_dev       dev int32 [B]: position written by the append (seq_lens - 1)
+ *   seq_lens_dev  dev int32 [B]: lengths including the appended token
+ */
+typedef struct {
+  kc_layer_cache cache;
+  const void* k_new_dev; /* dev [B][1][Hkv][d] new K rows, or NULL: nothing is appended    */
+  const void* v_new_dev; /* dev [B][1][Hkv][d] new V rows (NULL iff k_new_dev is NULL)     */
+  const void* q_dev;     /* dev [B][H][d]                                                  */
+  float* out_dev;        /* dev fp32 [B][H][d]                                             */
+  int32_t* idx_out_dev;  /* optional dev int32 [B][H][N]; unused for v_in_hbm layers       */
+  float* w_out_dev;      /* optional dev fp32 [B][H][N]; unused for v_in_hbm layers        */
+} kc_step_layer;
+
+int kcache_decode_step(kc_ctx* ctx, const kc_step_layer* layers, int32_t L, int32_t H,
+                       const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N,
+                       void* stream);
+
+/*
+ * The same step captured once into a HIP graph and replayed with one launch per
+ * decode step.  All pointers in `layers`, pos_dev and seq_lens_dev are baked into
+ * the graph; their contents may change between launches (the context grows by
+ * rewriting pos / seq_lens in place).  Options in effect at creation (rows, lanes)
+ * stay in effect for the graph; profiling events are not part of it.  The graph
+ * uses the context's workspace: do not run other calls of the same context
+ * concurrently with a launch.  Destroy graphs before the context.
+ */
+typedef struct kc_step_graph kc_step_graph;
+int kcache_step_graph_create(kc_ctx* ctx, const kc_step_layer* layers, int32_t L, int32_t H,
+                             const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N,
+                             kc_step_graph** out);
+int kcache_step_graph_launch(kc_ctx* ctx, kc_step_graph* graph, void* stream);
+int kcache_step_graph_destroy(kc_ctx* ctx, kc_step_graph* graph);
 
 /* Block until everything this context has enqueued (side streams included) is done. */
 int kcache_synchronize(kc_ctx* ctx);

@@ -14,6 +14,7 @@ GATHER_ZEROCOPY, GATHER_STAGED = 0, 1
 KERNELS = {"kscan": 0, "select": 1, "gather": 2, "store_k": 3, "store_v": 4, "fused": 5,
            "full": 6}
 OPT_PIPELINE_PARTS, OPT_PROFILE, OPT_STAGED_THREADS, OPT_FUSED, OPT_FUSED_ROWS = 0, 1, 2, 3, 4
+OPT_STEP_LANES = 5
 
 _c_i32, _c_i64, _c_p, _c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
 
@@ -27,6 +28,11 @@ class KCacheError(RuntimeError):
 class _CLayerCache(ctypes.Structure):
     _fields_ = [("k_dev", _c_p), ("v_host", _c_p), ("B", _c_i32), ("Hkv", _c_i32),
                 ("S_cap", _c_i32), ("d", _c_i32), ("dtype", _c_i32), ("v_in_hbm", _c_i32)]
+
+
+class _CStepLayer(ctypes.Structure):
+    _fields_ = [("cache", _CLayerCache), ("k_new_dev", _c_p), ("v_new_dev", _c_p),
+                ("q_dev", _c_p), ("out_dev", _c_p), ("idx_out_dev", _c_p), ("w_out_dev", _c_p)]
 
 
 _lib = None
@@ -61,6 +67,12 @@ def lib():
             "kcache_decode_attention": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_i32, _c_p, _c_i32,
                                                        _c_p, _c_p, _c_p, _c_i32, _c_p]),
             "kcache_full_attention": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_i32, _c_p, _c_p, _c_p]),
+            "kcache_decode_step": (ctypes.c_int, [_c_p, ctypes.POINTER(_CStepLayer), _c_i32, _c_i32,
+                                                  _c_p, _c_p, _c_i32, _c_p]),
+            "kcache_step_graph_create": (ctypes.c_int, [_c_p, ctypes.POINTER(_CStepLayer), _c_i32,
+                                                        _c_i32, _c_p, _c_p, _c_i32, pp]),
+            "kcache_step_graph_launch": (ctypes.c_int, [_c_p, _c_p, _c_p]),
+            "kcache_step_graph_destroy": (ctypes.c_int, [_c_p, _c_p]),
             "kcache_synchronize": (ctypes.c_int, [_c_p]),
             "kcache_device_check": (ctypes.c_int, [_c_p]),
             "kcache_profile_read": (ctypes.c_int, [_c_p, _c_i32, dbl_p, i64_p]),
@@ -108,6 +120,28 @@ class LayerCache:
         B, Hkv, S_cap, d = k_dev.shape
         self.c = _CLayerCache(k_dev.data_ptr(), v.data_ptr(), B, Hkv, S_cap, d,
                               _dtype_code(k_dev.dtype), 1 if self.v_in_hbm else 0)
+
+
+class StepGraph:
+    """A captured decode step (kcache_step_graph_*).  Keeps its tensors alive."""
+
+    def __init__(self, ctx, handle, keep):
+        self._ctx, self._h, self._keep = ctx, handle, keep
+
+    def launch(self, stream=None):
+        self._ctx._check(lib().kcache_step_graph_launch(self._ctx._h, self._h,
+                                                        _stream_ptr(stream)))
+
+    def close(self):
+        if self._h:
+            lib().kcache_step_graph_destroy(self._ctx._h, self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def _dtype_code(dt):
@@ -234,6 +268,37 @@ class Context:
         self._check(lib().kcache_full_attention(self._h, ctypes.byref(cache.c), _ptr(q), H,
                                                 _ptr(seq_lens), _ptr(out), _stream_ptr(stream)))
         return out
+
+    def set_step_lanes(self, lanes):
+        self.set_option(OPT_STEP_LANES, lanes)
+
+    @staticmethod
+    def _step_array(layers):
+        """layers: sequence of dicts with cache, q, out and optionally k_new, v_new, idx_out,
+        w_out (tensors).  Returns the C array; the caller keeps the tensors alive."""
+        arr = (_CStepLayer * len(layers))()
+        for i, y in enumerate(layers):
+            arr[i].cache = y["cache"].c
+            for field, key in (("k_new_dev", "k_new"), ("v_new_dev", "v_new"), ("q_dev", "q"),
+                               ("out_dev", "out"), ("idx_out_dev", "idx_out"),
+                               ("w_out_dev", "w_out")):
+                t = y.get(key)
+                setattr(arr[i], field, t.data_ptr() if t is not None else None)
+        return arr
+
+    def decode_step(self, layers, H, pos, seq_lens, N, stream=None):
+        """Append + attention for every layer in one call (see kcache_decode_step)."""
+        arr = self._step_array(layers)
+        self._check(lib().kcache_decode_step(self._h, arr, len(layers), H, _ptr(pos),
+                                             _ptr(seq_lens), int(N), _stream_ptr(stream)))
+
+    def step_graph(self, layers, H, pos, seq_lens, N):
+        """The same step captured into a HIP graph; returns a StepGraph to launch per step."""
+        arr = self._step_array(layers)
+        h = _c_p()
+        self._check(lib().kcache_step_graph_create(self._h, arr, len(layers), H, _ptr(pos),
+                                                   _ptr(seq_lens), int(N), ctypes.byref(h)))
+        return StepGraph(self, h, (list(layers), pos, seq_lens))
 
     def synchronize(self):
         self._check(lib().kcache_synchronize(self._h))

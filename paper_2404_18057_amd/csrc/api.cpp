@@ -96,6 +96,7 @@ struct ProfRec {
 };
 
 constexpr int kMaxParts = 64;
+constexpr int kMaxLanes = 4;
 
 }  // namespace
 
@@ -110,7 +111,11 @@ struct kc_ctx {
   size_t ws_bytes = 0;
   int* flags = nullptr;  // [0] device-check bits, [16] probe sink
   std::string err;
-  int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0;
+  int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 1;
+  int graphs = 0;          // live step graphs: they hold addresses inside ws / counters
+  bool capturing = false;  // a step is being captured into a graph: no profiling events
+  hipStream_t lane[kMaxLanes] = {};  // streams of kcache_decode_step with more than one lane
+  hipEvent_t ev_lane[kMaxLanes] = {};
   int* counters = nullptr;  // per KV unit arrival tickets of the fused kernel, zero when idle
   size_t counters_n = 0;
   std::vector<ProfRec> pending;
@@ -185,7 +190,7 @@ struct KernelTimer {
   hipStream_t st;
   hipEvent_t a = nullptr;
   KernelTimer(kc_ctx* c_, int id_, hipStream_t st_) : c(c_), id(id_), st(st_) {
-    if (c->profile && (a = get_event(c))) (void)hipEventRecord(a, st);
+    if (c->profile && !c->capturing && (a = get_event(c))) (void)hipEventRecord(a, st);
   }
   ~KernelTimer() {
     if (!a) return;
@@ -215,6 +220,10 @@ int collect_profile(kc_ctx* c) {
 
 int ensure_workspace(kc_ctx* c, size_t bytes) {
   if (bytes <= c->ws_bytes) return KC_OK;
+  if (c->graphs > 0)
+    return fail(c, KC_ERR_WORKSPACE, "the workspace would have to grow to %zu bytes while %d step "
+                "graph(s) hold addresses inside it: destroy them first, or create the context "
+                "with a larger workspace hint", bytes, c->graphs);
   KC_HIP(c, hipDeviceSynchronize());
   if (c->ws) (void)hipFree(c->ws);
   c->ws = nullptr;
@@ -226,8 +235,19 @@ int ensure_workspace(kc_ctx* c, size_t bytes) {
   return KC_OK;
 }
 
+int ensure_lanes(kc_ctx* c, int lanes) {
+  for (int i = 0; i < lanes; ++i) {
+    if (!c->lane[i]) KC_HIP(c, hipStreamCreateWithFlags(&c->lane[i], hipStreamNonBlocking));
+    if (!c->ev_lane[i]) KC_HIP(c, hipEventCreateWithFlags(&c->ev_lane[i], hipEventDisableTiming));
+  }
+  return KC_OK;
+}
+
 int ensure_counters(kc_ctx* c, size_t n) {
   if (n <= c->counters_n) return KC_OK;
+  if (c->graphs > 0)
+    return fail(c, KC_ERR_WORKSPACE, "the ticket counters would have to grow while %d step "
+                "graph(s) hold their address: destroy them first", c->graphs);
   KC_HIP(c, hipDeviceSynchronize());
   if (c->counters) (void)hipFree(c->counters);
   c->counters = nullptr;
@@ -344,6 +364,106 @@ int pick_parts(const kc_ctx* c, int kv_units, size_t k_bytes) {
   return std::max(p, 1);
 }
 
+
+// Sizes that a fused KCache launch of this shape needs.
+struct FusedPlan {
+  int R, chunks_cap, kk;
+  size_t bytes;
+};
+FusedPlan plan_fused(const kc_ctx* c, int B, int H, int Hkv, int S_cap, int N) {
+  const int G = H / Hkv;
+  FusedPlan p;
+  p.R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
+            ? c->fused_rows
+            : kc::fused_rows_per_block(B * Hkv, G, S_cap, N);
+  p.chunks_cap = (S_cap + p.R - 1) / p.R;
+  p.kk = std::min(N, p.R);
+  p.bytes = fused_bytes((size_t)B * H, p.chunks_cap, p.kk, N);
+  return p;
+}
+
+// One fused KCache launch on `st` with its scratch carved out of `ws` and its tickets in
+// `counters` (both exclusively this launch's until it has finished).
+int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, const void* q_dev,
+                  int H, const int32_t* seq_lens_dev, int N, float* out_dev, int32_t* idx_out_dev,
+                  float* w_out_dev, const FusedPlan& pl, void* ws, int* counters, hipStream_t st) {
+  const int B = cache->B, Hkv = cache->Hkv, S_cap = cache->S_cap;
+  const size_t units = (size_t)B * H;
+  char* p = static_cast<char*>(ws);
+  kc::FusedArgs a;
+  a.q = static_cast<const uint16_t*>(q_dev);
+  a.K = static_cast<const uint16_t*>(cache->k_dev);
+  a.V = static_cast<const uint16_t*>(v_map);
+  a.seq_lens = seq_lens_dev;
+  a.out = out_dev;
+  a.cand_z = reinterpret_cast<float*>(p);
+  p += round256(units * pl.chunks_cap * pl.kk * sizeof(float));
+  a.cand_pos = reinterpret_cast<int32_t*>(p);
+  p += round256(units * pl.chunks_cap * pl.kk * sizeof(float));
+  a.part = reinterpret_cast<float2*>(p);
+  p += round256(units * pl.chunks_cap * sizeof(float2));
+  a.idx = idx_out_dev ? idx_out_dev : reinterpret_cast<int32_t*>(p);
+  p += round256(units * N * sizeof(int32_t));
+  a.w = w_out_dev ? w_out_dev : reinterpret_cast<float*>(p);
+  a.counters = counters;
+  a.flags = c->flags;
+  a.H = H;
+  a.Hkv = Hkv;
+  a.S_cap = S_cap;
+  a.N = N;
+  a.R = pl.R;
+  a.chunks_cap = pl.chunks_cap;
+  a.kk = pl.kk;
+  a.kv0 = 0;
+  a.kv_count = B * Hkv;
+  a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
+  KernelTimer t(c, KC_KERNEL_FUSED, st);
+  KC_HIP(c, kc::launch_fused(a, cache->dtype, B * Hkv, st));
+  return KC_OK;
+}
+
+struct FullPlan {
+  int R, chunks_cap;
+  size_t part_bytes, bytes;
+};
+FullPlan plan_full(const kc_ctx* c, int B, int H, int Hkv, int S_cap) {
+  const int G = H / Hkv;
+  FullPlan p;
+  p.R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
+            ? c->fused_rows
+            : kc::full_rows_per_block(B * Hkv, G, S_cap);
+  p.chunks_cap = (S_cap + p.R - 1) / p.R;
+  const size_t units = (size_t)B * H;
+  p.part_bytes = round256(units * p.chunks_cap * sizeof(float2));
+  p.bytes = p.part_bytes + round256(units * p.chunks_cap * kc::kHeadDim * sizeof(float));
+  return p;
+}
+
+int enqueue_full(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, const void* q_dev,
+                 int H, const int32_t* seq_lens_dev, float* out_dev, const FullPlan& pl, void* ws,
+                 int* counters, hipStream_t st) {
+  kc::FullArgs a;
+  a.q = static_cast<const uint16_t*>(q_dev);
+  a.K = static_cast<const uint16_t*>(cache->k_dev);
+  a.V = static_cast<const uint16_t*>(v_map);
+  a.seq_lens = seq_lens_dev;
+  a.out = out_dev;
+  a.part = reinterpret_cast<float2*>(ws);
+  a.part_o = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.part_bytes);
+  a.counters = counters;
+  a.flags = c->flags;
+  a.H = H;
+  a.Hkv = cache->Hkv;
+  a.S_cap = cache->S_cap;
+  a.R = pl.R;
+  a.chunks_cap = pl.chunks_cap;
+  a.kv_count = cache->B * cache->Hkv;
+  a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
+  KernelTimer t(c, KC_KERNEL_FULL, st);
+  KC_HIP(c, kc::launch_full(a, cache->dtype, st));
+  return KC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -435,6 +555,10 @@ int kcache_destroy(kc_ctx* c) {
     if (e) (void)hipEventDestroy(e);
   for (auto e : c->ev_part)
     if (e) (void)hipEventDestroy(e);
+  for (auto e : c->ev_lane)
+    if (e) (void)hipEventDestroy(e);
+  for (auto st : c->lane)
+    if (st) (void)hipStreamDestroy(st);
   if (c->side) (void)hipStreamDestroy(c->side);
   if (c->store_side) (void)hipStreamDestroy(c->store_side);
   if (c->ws) (void)hipFree(c->ws);
@@ -462,6 +586,11 @@ int kcache_set_option(kc_ctx* c, int32_t option, int64_t value) {
       return KC_OK;
     case KC_OPT_FUSED:
       c->fused = value != 0;
+      return KC_OK;
+    case KC_OPT_STEP_LANES:
+      if (value < 1 || value > kMaxLanes)
+        return fail(c, KC_ERR_INVALID_ARG, "step lanes must be in [1, %d]", kMaxLanes);
+      c->step_lanes = (int)value;
       return KC_OK;
     case KC_OPT_FUSED_ROWS:
       if (value < 0 || value > kc::kFusedZFloats || value % kc::kFusedThreads != 0)
@@ -564,11 +693,8 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
   const int kv_units = B * Hkv;
   const bool staged = gather_mode == KC_GATHER_STAGED;
   const bool fused = !staged && c->fused;
-  const int R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
-                    ? c->fused_rows
-                    : kc::fused_rows_per_block(kv_units, G, S_cap, N);
-  const int chunks_cap = (S_cap + R - 1) / R, kk = std::min(N, R);
-  const size_t need = fused ? fused_bytes(units, chunks_cap, kk, N) : unfused_bytes(units, S_cap, N);
+  const FusedPlan pl = plan_fused(c, B, H, Hkv, S_cap, N);
+  const size_t need = fused ? pl.bytes : unfused_bytes(units, S_cap, N);
   if ((rc = ensure_workspace(c, need)) != KC_OK) return rc;
   if (staged && (rc = ensure_staged(c, units * N)) != KC_OK) return rc;
   if (fused && (rc = ensure_counters(c, kv_units)) != KC_OK) return rc;
@@ -585,38 +711,9 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
   }
 
   if (fused) {
-    char* p = static_cast<char*>(c->ws);
-    kc::FusedArgs a;
-    a.q = static_cast<const uint16_t*>(q_dev);
-    a.K = static_cast<const uint16_t*>(cache->k_dev);
-    a.V = static_cast<const uint16_t*>(v_map);
-    a.seq_lens = seq_lens_dev;
-    a.out = out_dev;
-    a.cand_z = reinterpret_cast<float*>(p);
-    p += round256(units * chunks_cap * kk * sizeof(float));
-    a.cand_pos = reinterpret_cast<int32_t*>(p);
-    p += round256(units * chunks_cap * kk * sizeof(float));
-    a.part = reinterpret_cast<float2*>(p);
-    p += round256(units * chunks_cap * sizeof(float2));
-    a.idx = idx_out_dev ? idx_out_dev : reinterpret_cast<int32_t*>(p);
-    p += round256(units * N * sizeof(int32_t));
-    a.w = w_out_dev ? w_out_dev : reinterpret_cast<float*>(p);
-    a.counters = c->counters;
-    a.flags = c->flags;
-    a.H = H;
-    a.Hkv = Hkv;
-    a.S_cap = S_cap;
-    a.N = N;
-    a.R = R;
-    a.chunks_cap = chunks_cap;
-    a.kk = kk;
-    a.kv0 = 0;
-    a.kv_count = kv_units;
-    a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
-    {
-      KernelTimer t(c, KC_KERNEL_FUSED, st);
-      KC_HIP(c, kc::launch_fused(a, cache->dtype, kv_units, st));
-    }
+    if ((rc = enqueue_fused(c, cache, v_map, q_dev, H, seq_lens_dev, N, out_dev, idx_out_dev,
+                            w_out_dev, pl, c->ws, c->counters, st)) != KC_OK)
+      return rc;
     KC_HIP(c, hipEventRecord(c->ev_last, st));
     c->have_last = true;
     return KC_OK;
@@ -743,17 +840,9 @@ int kcache_full_attention(kc_ctx* c, const kc_layer_cache* cache, const void* q_
   void* v_map = nullptr;
   if ((rc = v_pointer(c, cache, &v_map)) != KC_OK) return rc;
 
-  const int B = cache->B, Hkv = cache->Hkv, S_cap = cache->S_cap, G = H / Hkv;
-  const size_t units = (size_t)B * H;
-  const int kv_units = B * Hkv;
-  const int R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
-                    ? c->fused_rows
-                    : kc::full_rows_per_block(kv_units, G, S_cap);
-  const int chunks_cap = (S_cap + R - 1) / R;
-  const size_t part_bytes = round256(units * chunks_cap * sizeof(float2));
-  const size_t need = part_bytes + round256(units * chunks_cap * kc::kHeadDim * sizeof(float));
-  if ((rc = ensure_workspace(c, need)) != KC_OK) return rc;
-  if ((rc = ensure_counters(c, kv_units)) != KC_OK) return rc;
+  const FullPlan pl = plan_full(c, cache->B, H, cache->Hkv, cache->S_cap);
+  if ((rc = ensure_workspace(c, pl.bytes)) != KC_OK) return rc;
+  if ((rc = ensure_counters(c, (size_t)cache->B * cache->Hkv)) != KC_OK) return rc;
 
   hipStream_t st = (hipStream_t)stream;
   if (c->have_last) KC_HIP(c, hipStreamWaitEvent(st, c->ev_last, 0));
@@ -761,29 +850,205 @@ int kcache_full_attention(kc_ctx* c, const kc_layer_cache* cache, const void* q_
     KC_HIP(c, hipStreamWaitEvent(st, c->ev_store, 0));
     c->store_pending = false;
   }
-  kc::FullArgs a;
-  a.q = static_cast<const uint16_t*>(q_dev);
-  a.K = static_cast<const uint16_t*>(cache->k_dev);
-  a.V = static_cast<const uint16_t*>(v_map);
-  a.seq_lens = seq_lens_dev;
-  a.out = out_dev;
-  a.part = reinterpret_cast<float2*>(c->ws);
-  a.part_o = reinterpret_cast<float*>(static_cast<char*>(c->ws) + part_bytes);
-  a.counters = c->counters;
-  a.flags = c->flags;
-  a.H = H;
-  a.Hkv = Hkv;
-  a.S_cap = S_cap;
-  a.R = R;
-  a.chunks_cap = chunks_cap;
-  a.kv_count = kv_units;
-  a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
-  {
-    KernelTimer t(c, KC_KERNEL_FULL, st);
-    KC_HIP(c, kc::launch_full(a, cache->dtype, st));
-  }
+  if ((rc = enqueue_full(c, cache, v_map, q_dev, H, seq_lens_dev, out_dev, pl, c->ws, c->counters,
+                         st)) != KC_OK)
+    return rc;
   KC_HIP(c, hipEventRecord(c->ev_last, st));
   c->have_last = true;
+  return KC_OK;
+}
+
+}  // extern "C"
+
+struct kc_step_graph {
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+};
+
+namespace {
+
+// Validates a step and sizes what it needs; fills the device-visible V addresses.
+int prepare_step(kc_ctx* c, const char* who, const kc_step_layer* layers, int32_t L, int32_t H,
+                 const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N, int lanes,
+                 std::vector<void*>* v_maps, size_t* lane_bytes, size_t* lane_counters) {
+  if (!layers || L < 1) return fail(c, KC_ERR_INVALID_ARG, "%s: no layers", who);
+  if (!pos_dev || !seq_lens_dev) return fail(c, KC_ERR_INVALID_ARG, "%s: NULL pointer argument", who);
+  size_t need = 0, kv_max = 0;
+  v_maps->assign(L, nullptr);
+  for (int l = 0; l < L; ++l) {
+    const kc_step_layer& y = layers[l];
+    const char* why;
+    int rc = shape_status(&y.cache, H == 0 ? -1 : H, N, &why);
+    if (rc != KC_OK) return fail(c, rc, "%s: layer %d: %s", who, l, why);
+    if (!y.cache.k_dev || !y.cache.v_host || !y.q_dev || !y.out_dev)
+      return fail(c, KC_ERR_INVALID_ARG, "%s: layer %d: NULL pointer argument", who, l);
+    if ((y.k_new_dev == nullptr) != (y.v_new_dev == nullptr))
+      return fail(c, KC_ERR_INVALID_ARG, "%s: layer %d: k_new_dev and v_new_dev must both be "
+                  "given or both be NULL", who, l);
+    if (y.cache.B != layers[0].cache.B)
+      return fail(c, KC_ERR_INVALID_ARG, "%s: layer %d: B differs from layer 0", who, l);
+    if ((rc = v_pointer(c, &y.cache, &(*v_maps)[l])) != KC_OK) return rc;
+    need = std::max(need, y.cache.v_in_hbm
+                              ? plan_full(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap).bytes
+                              : plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N).bytes);
+    kv_max = std::max(kv_max, (size_t)y.cache.B * y.cache.Hkv);
+  }
+  *lane_bytes = round256(need);
+  *lane_counters = (kv_max + 63) & ~(size_t)63;
+  int rc = ensure_workspace(c, *lane_bytes * lanes);
+  if (rc != KC_OK) return rc;
+  if ((rc = ensure_counters(c, *lane_counters * lanes)) != KC_OK) return rc;
+  if (lanes > 1 && (rc = ensure_lanes(c, lanes)) != KC_OK) return rc;
+  return KC_OK;
+}
+
+// Enqueues the step on `st` (and, with lanes > 1, on the lane streams forked from and
+// joined back into `st`).  Allocates nothing: usable under stream capture.
+int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
+                 const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N, int lanes,
+                 const std::vector<void*>& v_maps, size_t lane_bytes, size_t lane_counters,
+                 hipStream_t st) {
+  if (lanes > 1) {
+    KC_HIP(c, hipEventRecord(c->ev_fork, st));
+    for (int i = 0; i < lanes; ++i) KC_HIP(c, hipStreamWaitEvent(c->lane[i], c->ev_fork, 0));
+  }
+  for (int l = 0; l < L; ++l) {
+    const kc_step_layer& y = layers[l];
+    const int ln = l % lanes;
+    hipStream_t s = lanes > 1 ? c->lane[ln] : st;
+    void* ws = static_cast<char*>(c->ws) + lane_bytes * ln;
+    int* counters = c->counters + lane_counters * ln;
+    if (y.k_new_dev) {
+      const kc::Shape sh{y.cache.B, 0, y.cache.Hkv, y.cache.S_cap, 0, y.cache.dtype};
+      KernelTimer t(c, KC_KERNEL_STORE_K, s);
+      KC_HIP(c, kc::launch_store(sh, y.k_new_dev, y.cache.k_dev, y.v_new_dev, v_maps[l], pos_dev, 1,
+                                 c->flags, y.cache.v_in_hbm ? 0 : 1, s));
+    }
+    int rc;
+    if (y.cache.v_in_hbm) {
+      const FullPlan pl = plan_full(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap);
+      rc = enqueue_full(c, &y.cache, v_maps[l], y.q_dev, H, seq_lens_dev, y.out_dev, pl, ws,
+                        counters, s);
+    } else {
+      const FusedPlan pl = plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N);
+      rc = enqueue_fused(c, &y.cache, v_maps[l], y.q_dev, H, seq_lens_dev, N, y.out_dev,
+                         y.idx_out_dev, y.w_out_dev, pl, ws, counters, s);
+    }
+    if (rc != KC_OK) return rc;
+  }
+  if (lanes > 1) {
+    for (int i = 0; i < lanes; ++i) {
+      KC_HIP(c, hipEventRecord(c->ev_lane[i], c->lane[i]));
+      KC_HIP(c, hipStreamWaitEvent(st, c->ev_lane[i], 0));
+    }
+  }
+  return KC_OK;
+}
+
+int wait_for_earlier_work(kc_ctx* c, hipStream_t st) {
+  if (c->have_last) KC_HIP(c, hipStreamWaitEvent(st, c->ev_last, 0));
+  if (c->store_pending) {
+    KC_HIP(c, hipStreamWaitEvent(st, c->ev_store, 0));
+    c->store_pending = false;
+  }
+  return KC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kcache_decode_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
+                       const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N,
+                       void* stream) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  DeviceGuard g(c->device);
+  if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  std::vector<void*> v_maps;
+  size_t lane_bytes = 0, lane_counters = 0;
+  const int lanes = std::min<int>(c->step_lanes, std::max(L, 1));
+  int rc = prepare_step(c, "kcache_decode_step", layers, L, H, pos_dev, seq_lens_dev, N, lanes,
+                        &v_maps, &lane_bytes, &lane_counters);
+  if (rc != KC_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  if ((rc = wait_for_earlier_work(c, st)) != KC_OK) return rc;
+  if ((rc = enqueue_step(c, layers, L, H, pos_dev, seq_lens_dev, N, lanes, v_maps, lane_bytes,
+                         lane_counters, st)) != KC_OK)
+    return rc;
+  KC_HIP(c, hipEventRecord(c->ev_last, st));
+  c->have_last = true;
+  return KC_OK;
+}
+
+int kcache_step_graph_create(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
+                             const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N,
+                             kc_step_graph** out) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  if (!out) return fail(c, KC_ERR_INVALID_ARG, "kcache_step_graph_create: out is NULL");
+  DeviceGuard g(c->device);
+  if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  std::vector<void*> v_maps;
+  size_t lane_bytes = 0, lane_counters = 0;
+  const int lanes = std::min<int>(c->step_lanes, std::max(L, 1));
+  int rc = prepare_step(c, "kcache_step_graph_create", layers, L, H, pos_dev, seq_lens_dev, N,
+                        lanes, &v_maps, &lane_bytes, &lane_counters);
+  if (rc != KC_OK) return rc;
+  // everything the context still has in flight is finished first, so that the captured
+  // work depends on nothing outside the graph
+  KC_HIP(c, hipDeviceSynchronize());
+  c->have_last = false;
+  c->store_pending = false;
+  KC_HIP(c, hipStreamBeginCapture(c->side, hipStreamCaptureModeThreadLocal));
+  c->capturing = true;
+  rc = enqueue_step(c, layers, L, H, pos_dev, seq_lens_dev, N, lanes, v_maps, lane_bytes,
+                    lane_counters, c->side);
+  c->capturing = false;
+  hipGraph_t graph = nullptr;
+  hipError_t e = hipStreamEndCapture(c->side, &graph);
+  if (rc != KC_OK) {
+    if (graph) (void)hipGraphDestroy(graph);
+    (void)hipGetLastError();
+    return rc;
+  }
+  if (e != hipSuccess || !graph)
+    return fail(c, KC_ERR_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+  kc_step_graph* sg = new kc_step_graph();
+  sg->graph = graph;
+  e = hipGraphInstantiate(&sg->exec, graph, nullptr, nullptr, 0);
+  if (e != hipSuccess) {
+    (void)hipGraphDestroy(graph);
+    delete sg;
+    return fail(c, KC_ERR_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+  }
+  c->graphs += 1;
+  *out = sg;
+  return KC_OK;
+}
+
+int kcache_step_graph_launch(kc_ctx* c, kc_step_graph* sg, void* stream) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  if (!sg || !sg->exec) return fail(c, KC_ERR_INVALID_ARG, "kcache_step_graph_launch: no graph");
+  DeviceGuard g(c->device);
+  if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  hipStream_t st = (hipStream_t)stream;
+  int rc = wait_for_earlier_work(c, st);
+  if (rc != KC_OK) return rc;
+  KC_HIP(c, hipGraphLaunch(sg->exec, st));
+  KC_HIP(c, hipEventRecord(c->ev_last, st));
+  c->have_last = true;
+  return KC_OK;
+}
+
+int kcache_step_graph_destroy(kc_ctx* c, kc_step_graph* sg) {
+  if (!sg) return KC_OK;
+  if (c) {
+    DeviceGuard g(c->device);
+    (void)hipDeviceSynchronize();
+    if (c->graphs > 0) c->graphs -= 1;
+  }
+  if (sg->exec) (void)hipGraphExecDestroy(sg->exec);
+  if (sg->graph) (void)hipGraphDestroy(sg->graph);
+  delete sg;
   return KC_OK;
 }
 
@@ -792,6 +1057,8 @@ int kcache_synchronize(kc_ctx* c) {
   DeviceGuard g(c->device);
   KC_HIP(c, hipStreamSynchronize(c->side));
   KC_HIP(c, hipStreamSynchronize(c->store_side));
+  for (auto st : c->lane)
+    if (st) KC_HIP(c, hipStreamSynchronize(st));
   if (c->have_last) KC_HIP(c, hipEventSynchronize(c->ev_last));
   return KC_OK;
 }

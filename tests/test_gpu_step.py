@@ -1,0 +1,193 @@
+"""GPU tests of the whole-step calls: kcache_decode_step and its HIP-graph form must give
+exactly what the per-layer calls give (same kernels, same launch shapes), including on
+replays of the graph with other work in between and with a growing context."""
+import numpy as np
+import pytest
+import torch
+
+import kcache_inputs as ki
+from harness import build_layer, oracle_unit, check_unit, sample_units
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def kc():
+    import paper_2404_18057_amd as kc
+    return kc
+
+
+@pytest.fixture(scope="module")
+def ctx(kc):
+    c = kc.Context(0)
+    yield c
+    c.close()
+
+
+def make_model(kc, ctx, wl, L, hbm_layers=0):
+    """L layers of one workload; the first hbm_layers keep V in HBM.  The last cached
+    position of every sequence is left for the step's own append."""
+    layers, gen = [], []
+    for l in range(L):
+        cache, q, lens, k, v = build_layer(ctx, wl, l)
+        if l < hbm_layers:
+            cache = kc.LayerCache(cache.k, cache.v.to(DEV))
+        lens_h = lens.cpu().numpy()
+        k_tok = torch.stack([k[b, :, lens_h[b] - 1] for b in range(wl.B)]).unsqueeze(1).contiguous()
+        v_tok = torch.stack([v[b, :, lens_h[b] - 1] for b in range(wl.B)]).unsqueeze(1).contiguous()
+        # wipe the last position so that the append is needed for a correct result
+        for b in range(wl.B):
+            cache.k[b, :, lens_h[b] - 1] = 0
+            cache.v[b, :, lens_h[b] - 1] = 0
+        layers.append(dict(cache=cache, q=q, k_new=k_tok, v_new=v_tok,
+                           out=torch.zeros((wl.B, wl.H, wl.d), dtype=torch.float32, device=DEV),
+                           idx_out=torch.zeros((wl.B, wl.H, wl.N), dtype=torch.int32, device=DEV),
+                           w_out=torch.zeros((wl.B, wl.H, wl.N), dtype=torch.float32, device=DEV)))
+        gen.append((k, v))
+    return layers, lens, gen
+
+
+def per_layer_reference(ctx, wl, layers, pos, lens):
+    outs = []
+    for y in layers:
+        ctx.prefill_store(y["cache"], y["k_new"], y["v_new"], pos)
+        if y["cache"].v_in_hbm:
+            o = ctx.full_attention(y["cache"], y["q"], lens)
+            outs.append((o.clone(), None, None))
+        else:
+            idx = torch.empty_like(y["idx_out"])
+            w = torch.empty_like(y["w_out"])
+            o = ctx.decode_attention(y["cache"], y["q"], lens, wl.N, idx_out=idx, w_out=w)
+            outs.append((o.clone(), idx, w))
+    torch.cuda.synchronize()
+    return outs
+
+
+def assert_same(layers, ref):
+    for y, (o, idx, w) in zip(layers, ref):
+        assert torch.equal(y["out"], o)
+        if idx is not None:
+            assert torch.equal(y["idx_out"], idx) and torch.equal(y["w_out"], w)
+
+
+def wipe_last(layers, lens):
+    """Zeroes the newest cached position again, so that only a working append restores it."""
+    lens_h = lens.cpu().numpy()
+    for y in layers:
+        for b in range(len(lens_h)):
+            y["cache"].k[b, :, lens_h[b] - 1] = 0
+            y["cache"].v[b, :, lens_h[b] - 1] = 0
+    torch.cuda.synchronize()
+
+
+def clear(layers):
+    for y in layers:
+        y["out"].fill_(float("nan"))
+        y["idx_out"].fill_(-5)
+        y["w_out"].fill_(-5.0)
+
+
+@pytest.mark.parametrize("lanes", [1, 2, 3])
+def test_step_equals_per_layer_calls_and_oracle(kc, ctx, lanes):
+    wl = ki.config(1, B=2, S_cap=3000)
+    L = 5
+    layers, lens, _ = make_model(kc, ctx, wl, L, hbm_layers=2)
+    pos = (lens - 1).to(torch.int32)
+    ref = per_layer_reference(ctx, wl, layers, pos, lens)
+    clear(layers)
+    wipe_last(layers, lens)
+    ctx.set_step_lanes(lanes)
+    ctx.decode_step(layers, wl.H, pos, lens, wl.N)
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    ctx.set_step_lanes(1)
+    ctx.device_check()
+    assert_same(layers, ref)
+    # and against the oracle, on a KCache layer, through the step call
+    y = layers[3]
+    out, idx, w = y["out"].cpu().numpy(), y["idx_out"].cpu().numpy(), y["w_out"].cpu().numpy()
+    for (b, h) in sample_units(wl, 6):
+        r = oracle_unit(wl, 3, b, h, wl.N)
+        check_unit(r, wl.N, out[b, h], idx[b, h], w[b, h], tag="step layer 3 (%d,%d)" % (b, h))
+
+
+@pytest.mark.parametrize("lanes", [1, 2])
+def test_graph_replays_equal_eager_results_with_work_in_between(kc, ctx, lanes):
+    wl = ki.config(1, B=2, S_cap=2500)
+    L = 4
+    layers, lens, gen = make_model(kc, ctx, wl, L, hbm_layers=1)
+    lens = lens.clone()
+    lens[1] = 1800                      # room to grow
+    pos = (lens - 1).to(torch.int32)
+    ctx.set_step_lanes(lanes)
+    graph = ctx.step_graph(layers, wl.H, pos, lens, wl.N)
+    ctx.set_step_lanes(1)
+    other = kc.Context(0)               # eager reference on its own workspace
+    try:
+        for rep in range(4):
+            # new token rows for this step: take them from the generated tensors
+            lens_h = lens.cpu().numpy()
+            for l, y in enumerate(layers):
+                k, v = gen[l]
+                for b in range(wl.B):
+                    y["k_new"][b, 0] = k[b, :, lens_h[b] - 1]
+                    y["v_new"][b, 0] = v[b, :, lens_h[b] - 1]
+            ref = per_layer_reference(other, wl, layers, pos, lens)
+            other.synchronize()
+            clear(layers)
+            wipe_last(layers, lens)
+            graph.launch()
+            ctx.synchronize()
+            torch.cuda.synchronize()
+            assert_same(layers, ref)
+            # unrelated eager work of the program between replays
+            _ = (layers[0]["q"].float() @ layers[0]["q"].float().transpose(1, 2)).sum().item()
+            # the context grows in place: same graph, new lengths
+            if rep < 3 and int(lens[1]) < wl.S_cap:
+                lens[1] += 1
+                pos.copy_(lens - 1)
+        ctx.device_check()
+    finally:
+        graph.close()
+        other.close()
+
+
+def test_workspace_cannot_grow_under_a_live_graph(kc):
+    c = kc.Context(0)
+    try:
+        wl = ki.config(1, B=1, S_cap=1024)
+        layers, lens, _ = make_model(kc, c, wl, 1)
+        pos = (lens - 1).to(torch.int32)
+        graph = c.step_graph(layers, wl.H, pos, lens, wl.N)
+        big = ki.config(1, B=4, S_cap=4096)
+        cache, q, blens, _, _ = build_layer(kc.Context(0), big, 0)
+        with pytest.raises(kc.KCacheError) as e:
+            c.decode_attention(cache, q, blens, 512)
+        assert e.value.status == -4
+        graph.launch()
+        c.synchronize()
+        graph.close()
+        c.decode_attention(cache, q, blens, 512)      # allowed again
+        c.synchronize()
+    finally:
+        c.close()
+
+
+def test_step_error_paths(kc, ctx):
+    wl = ki.config(1)
+    layers, lens, _ = make_model(kc, ctx, wl, 2)
+    pos = (lens - 1).to(torch.int32)
+    with pytest.raises(kc.KCacheError) as e:
+        ctx.decode_step([], wl.H, pos, lens, wl.N)
+    assert e.value.status == -1
+    bad = [dict(layers[0]), dict(layers[1])]
+    bad[1]["v_new"] = None
+    with pytest.raises(kc.KCacheError) as e:
+        ctx.decode_step(bad, wl.H, pos, lens, wl.N)
+    assert e.value.status == -1
+    with pytest.raises(kc.KCacheError):
+        ctx.set_step_lanes(9)
+    with pytest.raises(kc.KCacheError) as e:
+        ctx.decode_step(layers, 3, pos, lens, wl.N)   # H not a multiple of Hkv
+    assert e.value.status == -1
