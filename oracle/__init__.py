@@ -38,6 +38,8 @@ def _load():
         lib.kcache_oracle_unit.argtypes = [c_p, c_p, c_p, ctypes.c_int, c_i32, c_i32, c_i32,
                                            c_p, c_p, c_p, c_p, c_p]
         lib.kcache_oracle_unit.restype = ctypes.c_int
+        lib.kcache_oracle_unit_renormalised.argtypes = lib.kcache_oracle_unit.argtypes
+        lib.kcache_oracle_unit_renormalised.restype = ctypes.c_int
         lib.kcache_oracle_decode.argtypes = [c_p, c_p, c_p, ctypes.c_int, c_i32, c_i32, c_i32,
                                              c_i32, c_i32, c_p, c_i32, c_p, c_p, c_p, ctypes.c_int]
         lib.kcache_oracle_decode.restype = ctypes.c_int
@@ -72,11 +74,12 @@ def decode16(bits, dtype):
     return out
 
 
-def decode_unit(q, K, V, dtype, N, want_scores=False):
+def decode_unit(q, K, V, dtype, N, want_scores=False, renormalise=False):
     """One (sequence, head) unit.  q [d], K [s][d], V [s][d] as uint16 bits.
 
     Returns dict(out [d] f64, idx [N] i32 ascending / -1 padded, w [N] f64,
-    and with want_scores: z [s], p [s])."""
+    and with want_scores: z [s], p [s]).  renormalise selects the variant whose kept
+    weights are divided by their sum."""
     q, K, V = _u16(q), _u16(K), _u16(V)
     s, d = K.shape
     assert q.shape == (d,) and V.shape == (s, d)
@@ -85,9 +88,9 @@ def decode_unit(q, K, V, dtype, N, want_scores=False):
     w = np.empty(N, np.float64)
     z = np.empty(s, np.float64) if want_scores else None
     p = np.empty(s, np.float64) if want_scores else None
-    rc = _load().kcache_oracle_unit(_ptr(q), _ptr(K), _ptr(V), dtype, s, d, N, _ptr(out),
-                                    _ptr(idx), _ptr(w), _ptr(z) if want_scores else None,
-                                    _ptr(p) if want_scores else None)
+    fn = _load().kcache_oracle_unit_renormalised if renormalise else _load().kcache_oracle_unit
+    rc = fn(_ptr(q), _ptr(K), _ptr(V), dtype, s, d, N, _ptr(out), _ptr(idx), _ptr(w),
+            _ptr(z) if want_scores else None, _ptr(p) if want_scores else None)
     if rc != 0:
         raise ValueError("kcache_oracle_unit rejected its arguments")
     res = dict(out=out, idx=idx, w=w)

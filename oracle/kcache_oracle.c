@@ -115,9 +115,9 @@ static int kco_cmp_i32(const void* a, const void* b) {
  *   p_out  [s]      optional (may be NULL): full softmax
  * Returns 0, or -1 on bad arguments / allocation failure.
  */
-int kcache_oracle_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, int dtype,
-                       int32_t s, int32_t d, int32_t N, double* out, int32_t* idx, double* w,
-                       double* z_out, double* p_out) {
+static int kco_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, int dtype, int32_t s,
+                    int32_t d, int32_t N, int renormalise, double* out, int32_t* idx, double* w,
+                    double* z_out, double* p_out) {
   if (!q || !K || !V || !out || !idx || !w || s < 1 || d < 1 || N < 1) return -1;
   double* z = (double*)malloc(sizeof(double) * (size_t)s);
   double* p = (double*)malloc(sizeof(double) * (size_t)s);
@@ -160,7 +160,11 @@ int kcache_oracle_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, 
   qsort(idx, (size_t)n_eff, sizeof(int32_t), kco_cmp_i32);
   for (int32_t j = n_eff; j < N; ++j) idx[j] = -1;
 
-  /* weighted sum of the selected V rows, weights NOT renormalised */
+  /* weighted sum of the selected V rows; the weights are the full-context softmax values
+     (NOT renormalised) unless the variant is asked for, which divides them by their sum */
+  double kept = 0.0;
+  for (int32_t j = 0; j < n_eff; ++j) kept += p[idx[j]];
+  const double divisor = renormalise ? kept : 1.0;
   for (int32_t c = 0; c < d; ++c) out[c] = 0.0;
   for (int32_t j = 0; j < N; ++j) {
     if (j >= n_eff) {
@@ -168,14 +172,33 @@ int kcache_oracle_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, 
       continue;
     }
     int32_t t = idx[j];
-    w[j] = p[t];
-    for (int32_t c = 0; c < d; ++c) out[c] += p[t] * kco_decode(V[(size_t)t * d + c], dtype);
+    w[j] = p[t] / divisor;
+    for (int32_t c = 0; c < d; ++c) out[c] += w[j] * kco_decode(V[(size_t)t * d + c], dtype);
   }
 
   if (z_out) memcpy(z_out, z, sizeof(double) * (size_t)s);
   if (p_out) memcpy(p_out, p, sizeof(double) * (size_t)s);
   free(z); free(p); free(qd); free(order);
   return 0;
+}
+
+int kcache_oracle_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, int dtype,
+                       int32_t s, int32_t d, int32_t N, double* out, int32_t* idx, double* w,
+                       double* z_out, double* p_out) {
+  return kco_unit(q, K, V, dtype, s, d, N, 0, out, idx, w, z_out, p_out);
+}
+
+/*
+ * Variant of the unit above in which the N kept weights are divided by their sum,
+ * so that they add up to one.  The paper's formula does not do this (Table 1:
+ * TopN applied to the softmax output); its remark in section 4 that TopN
+ * "regularized the softmax" is the only hint at such a variant.  Everything up
+ * to and including the selection is identical.
+ */
+int kcache_oracle_unit_renormalised(const uint16_t* q, const uint16_t* K, const uint16_t* V,
+                                    int dtype, int32_t s, int32_t d, int32_t N, double* out,
+                                    int32_t* idx, double* w, double* z_out, double* p_out) {
+  return kco_unit(q, K, V, dtype, s, d, N, 1, out, idx, w, z_out, p_out);
 }
 
 /*

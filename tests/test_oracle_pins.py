@@ -421,3 +421,40 @@ def test_conventional_attention_batch_gqa_ragged_and_padding():
             assert np.array_equal(out[b, h], ref)
     with pytest.raises(ValueError):
         oracle.full_attention(q, K, V, F16, np.array([51, 1, 1], np.int32))
+
+
+# ---------------------------------------------------------------- renormalised variant
+def test_renormalised_variant_uniform_scores_closed_form():
+    # identical K rows: kept weights become 1/N each, out = mean of the first N V rows
+    rng = np.random.default_rng(95)
+    s, d, N = 40, 16, 8
+    q = bits(rng.standard_normal(d))
+    K = np.tile(bits(rng.standard_normal(d)), (s, 1))
+    Vf = np.round(rng.standard_normal((s, d)) * 16) / 16
+    r = oracle.decode_unit(q, K, bits(Vf), F16, N, renormalise=True)
+    assert r["idx"].tolist() == list(range(N))
+    assert np.allclose(r["w"], 1.0 / N, rtol=1e-14)
+    assert np.allclose(r["out"], Vf[:N].mean(0), rtol=0, atol=1e-14)
+
+
+def test_renormalised_variant_n_one_returns_the_argmax_row_exactly():
+    rng = np.random.default_rng(96)
+    q, K, V = rand_unit(rng, 50, 32)
+    r = oracle.decode_unit(q, K, V, F16, 1, renormalise=True, want_scores=True)
+    t = int(np.argmax(r["z"]))
+    assert r["idx"].tolist() == [t] and r["w"][0] == 1.0
+    assert np.array_equal(r["out"], back(V[t]))
+
+
+def test_renormalised_variant_is_the_literal_one_rescaled_and_full_attention_at_n_equal_s():
+    rng = np.random.default_rng(97)
+    q, K, V = rand_unit(rng, 120, 64, BF16)
+    a = oracle.decode_unit(q, K, V, BF16, 17)
+    b = oracle.decode_unit(q, K, V, BF16, 17, renormalise=True)
+    assert np.array_equal(a["idx"], b["idx"])
+    assert abs(b["w"].sum() - 1.0) < 1e-14
+    assert np.allclose(b["w"], a["w"] / a["w"].sum(), rtol=1e-14)
+    assert np.allclose(b["out"], a["out"] / a["w"].sum(), rtol=1e-12, atol=1e-15)
+    full = oracle.full_unit(q, K, V, BF16)
+    assert np.allclose(oracle.decode_unit(q, K, V, BF16, 120, renormalise=True)["out"], full,
+                       rtol=1e-12, atol=1e-14)
