@@ -99,6 +99,11 @@ typedef enum {
   KC_OPT_FUSED_ROWS = 4,     /* positions scored per workgroup of the fused launch: a
                                 multiple of 512 with rows * (H/Hkv) <= 8192, or 0 =
                                 choose from the shape (default)                        */
+  KC_OPT_RENORMALIZE = 6,    /* 0 (default): the kept weights are the full-context softmax
+                                values, as Table 1 writes them; 1: variant that divides
+                                the N kept weights by their sum (section 4 remarks that
+                                TopN "regularized" the softmax; the paper does not say
+                                it renormalises)                                      */
   KC_OPT_STEP_LANES = 5      /* kcache_decode_step / kcache_step_graph_create: 1 (default)
                                 runs the layers one after another on the caller's
                                 stream; 2..4 deals them over that many internal streams

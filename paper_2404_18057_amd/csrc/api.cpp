@@ -111,7 +111,8 @@ struct kc_ctx {
   size_t ws_bytes = 0;
   int* flags = nullptr;  // [0] device-check bits, [16] probe sink
   std::string err;
-  int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 1;
+  int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 1,
+      renorm = 0;
   int graphs = 0;          // live step graphs: they hold addresses inside ws / counters
   bool capturing = false;  // a step is being captured into a graph: no profiling events
   hipStream_t lane[kMaxLanes] = {};  // streams of kcache_decode_step with more than one lane
@@ -416,6 +417,7 @@ int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, con
   a.kk = pl.kk;
   a.kv0 = 0;
   a.kv_count = B * Hkv;
+  a.renorm = c->renorm;
   a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
   KernelTimer t(c, KC_KERNEL_FUSED, st);
   KC_HIP(c, kc::launch_fused(a, cache->dtype, B * Hkv, st));
@@ -587,6 +589,9 @@ int kcache_set_option(kc_ctx* c, int32_t option, int64_t value) {
     case KC_OPT_FUSED:
       c->fused = value != 0;
       return KC_OK;
+    case KC_OPT_RENORMALIZE:
+      c->renorm = value != 0;
+      return KC_OK;
     case KC_OPT_STEP_LANES:
       if (value < 1 || value > kMaxLanes)
         return fail(c, KC_ERR_INVALID_ARG, "step lanes must be in [1, %d]", kMaxLanes);
@@ -700,7 +705,7 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
   if (fused && (rc = ensure_counters(c, kv_units)) != KC_OK) return rc;
 
   hipStream_t st = (hipStream_t)stream;
-  const kc::Shape sh{B, H, Hkv, S_cap, N, cache->dtype};
+  const kc::Shape sh{B, H, Hkv, S_cap, N, cache->dtype, c->renorm};
   const int parts = pick_parts(c, kv_units, (size_t)kv_units * S_cap * kc::kRowBytes);
 
   // the workspace and the V rows must be free of earlier work of this context

@@ -279,8 +279,10 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     // Candidate positions that did not fit in LDS are fetched after the selection,
     // all kept entries at once: emit() then records the candidate's index instead.
     const bool pos_later = !pos_in_lds && stage_out;
+    float kept = 0.f;  // this thread's share of the kept softmax mass (renormalised variant)
     auto emit = [&](int r, int i, float v) {
       const float w = expf(v - mx) * inv_Z;
+      kept += w;
       wu[r] = w;
       if (stage_out) stage_f[r] = w;
       if (pos_later) {
@@ -300,6 +302,23 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
         const int32_t t = ld_dev(cp + stage_i[r]);
         stage_i[r] = t;
         iu[r] = t;
+      }
+      __syncthreads();
+    }
+    if (a.renorm) {
+      // variant: divide the kept weights by their sum (equal maxima make the merge a sum)
+      const float inv = 1.f / block_merge_stats<FT>(0.f, kept, &sm.sc).y;
+      if (stage_out) {
+        for (int r = tid; r < n_eff; r += FT) {
+          const float w = stage_f[r] * inv;
+          stage_f[r] = w;
+          wu[r] = w;
+        }
+      } else {  // written by whichever thread found the entry: re-read around the L1
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        for (int r = tid; r < n_eff; r += FT) wu[r] = ld_dev(wu + r) * inv;
+        __builtin_amdgcn_s_waitcnt(0);
       }
       __syncthreads();
     }

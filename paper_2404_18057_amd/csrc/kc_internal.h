@@ -27,6 +27,7 @@ constexpr int kFlagBadPos = 2;
 
 struct Shape {
   int B, H, Hkv, S_cap, N, dtype;
+  int renorm = 0;  // 1: kept weights are divided by their sum
 };
 
 // Scores z[b][h][t] = (q[b][h] . K[b][h/G][t]) / sqrt(d_h) for the KV units
@@ -73,6 +74,7 @@ struct FusedArgs {
   int kk;          // min(N, R): candidates kept per chunk
   int kv0;
   int kv_count;    // KV units of this launch
+  int renorm;      // 1: kept weights are divided by their sum
   float scale;
 };
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N);

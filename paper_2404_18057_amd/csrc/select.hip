@@ -18,7 +18,7 @@ __global__ __launch_bounds__(NT) void select_kernel(const float* __restrict__ z,
                                                     const int32_t* __restrict__ seq_lens,
                                                     int32_t* __restrict__ idx,
                                                     float* __restrict__ wgt, int H, int S_cap,
-                                                    int N, int u0) {
+                                                    int N, int u0, int renorm) {
   __shared__ TopNScratch<NT> sc;
   const int unit = u0 + blockIdx.x;
   const int b = unit / H;
@@ -39,10 +39,23 @@ __global__ __launch_bounds__(NT) void select_kernel(const float* __restrict__ z,
   auto key = [&](int t) { return zr[t]; };
   const float2 ml = block_softmax_stats<NT>(key, s, &sc);
   const float m = ml.x, inv_Z = 1.f / ml.y;
+  float kept = 0.f;  // this thread's share of the kept softmax mass
   block_topn<NT, false>(key, s, n_eff, &sc, [&](int r, int t, float v) {
+    const float w = expf(v - m) * inv_Z;
     iu[r] = t;
-    wu[r] = expf(v - m) * inv_Z;
+    wu[r] = w;
+    kept += w;
   });
+  if (renorm) {
+    // variant: the kept weights are divided by their sum.  Entries were written by
+    // whichever thread found them, so they are re-read around the L1.
+    const float2 tot = block_merge_stats<NT>(0.f, kept, &sc);  // equal maxima: a plain sum
+    const float inv = 1.f / tot.y;
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    for (int r = tid; r < n_eff; r += NT)
+      wu[r] = __hip_atomic_load(&wu[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) * inv;
+  }
 }
 
 }  // namespace
@@ -51,7 +64,7 @@ hipError_t launch_select(const Shape& sh, const float* z, const int32_t* seq_len
                          float* w, int u0, int count, hipStream_t st) {
   if (count <= 0) return hipSuccess;
   hipLaunchKernelGGL(select_kernel, dim3((unsigned)count), dim3(NT), 0, st, z, seq_lens, idx, w,
-                     sh.H, sh.S_cap, sh.N, u0);
+                     sh.H, sh.S_cap, sh.N, u0, sh.renorm);
   return hipGetLastError();
 }
 

@@ -329,3 +329,39 @@ def test_bad_arguments_are_reported_not_fatal(kc, ctx):
     with pytest.raises(kc.KCacheError) as e:
         ctx.device_check()
     assert e.value.status == -6
+
+
+# ------------------------------------------------------------------ renormalised variant
+@pytest.mark.parametrize("gather_mode", [0, 1])
+def test_renormalised_variant_matches_its_oracle(kc, ctx, gather_mode):
+    """KC_OPT_RENORMALIZE divides the kept weights by their sum (the alternative reading of
+    the paper's remark that TopN regularises the softmax); same selection, same tolerance."""
+    if gather_mode == 1 and ctx.fused_default:
+        pytest.skip("the staged gather runs on the unfused path")
+    rng = np.random.default_rng(77)
+    B, H, S, d = 2, 3, 3000, 128
+    q = rng.standard_normal((B, H, d))
+    K = rng.standard_normal((B, H, S, d))
+    V = rng.standard_normal((B, H, S, d))
+    lens = [3000, 700]
+    ctx.set_renormalize(True)
+    try:
+        for N in (1, 40, 1500):   # 1500 > the 1024 entries the fused kernel stages in LDS
+            out, idx, w, (qb, kb, vb, code) = manual_case(kc, ctx, q, K, V, lens, N,
+                                                          gather_mode=gather_mode)
+            for b in range(B):
+                s = lens[b]
+                for h in range(H):
+                    r = oracle.decode_unit(qb[b, h], kb[b, h, :s], vb[b, h, :s], code, N,
+                                           want_scores=True, renormalise=True)
+                    n_eff = min(N, s)
+                    assert set(idx[b, h, :n_eff].tolist()) == set(r["idx"][:n_eff].tolist())
+                    assert abs(float(w[b, h].sum()) - 1.0) < 1e-4
+                    assert np.allclose(w[b, h], r["w"], rtol=2e-3, atol=1e-7)
+                    err = np.abs(out[b, h].astype(np.float64) - r["out"])
+                    assert (err <= 1e-3 + 2e-3 * np.abs(r["out"])).all()
+    finally:
+        ctx.set_renormalize(False)
+    # and the default is untouched afterwards: kept weights sum to less than one again
+    out, idx, w, _ = manual_case(kc, ctx, q, K, V, lens, 40)
+    assert float(w[0, 0].sum()) < 0.999
