@@ -191,3 +191,42 @@ def test_step_error_paths(kc, ctx):
     with pytest.raises(kc.KCacheError) as e:
         ctx.decode_step(layers, 3, pos, lens, wl.N)   # H not a multiple of Hkv
     assert e.value.status == -1
+
+
+def test_graph_launch_at_the_benchmark_shape_matches_the_oracle(kc):
+    """Config 2's per-layer shape (B 8, 32 heads, 32768 positions, N 256), two layers, issued
+    the way bench.py issues a step: one launch of the captured graph.  Sampled units against
+    the oracle with the acceptance rule of the parity tests."""
+    wl = ki.config(2)
+    c = kc.Context(0, kc.workspace_bytes(wl.B, wl.H, wl.S_cap, wl.N))
+    try:
+        layers, lens = [], None
+        for l in (0, wl.L - 1):
+            cache, q, lens, k, v = build_layer(c, wl, l, chunk_T=8192)
+            k_tok = k[:, :, wl.S_cap - 1].unsqueeze(1).contiguous()
+            v_tok = v[:, :, wl.S_cap - 1].unsqueeze(1).contiguous()
+            del k, v
+            layers.append(dict(cache=cache, q=q, k_new=k_tok, v_new=v_tok,
+                               out=torch.zeros((wl.B, wl.H, wl.d), dtype=torch.float32, device=DEV),
+                               idx_out=torch.zeros((wl.B, wl.H, wl.N), dtype=torch.int32, device=DEV),
+                               w_out=torch.zeros((wl.B, wl.H, wl.N), dtype=torch.float32, device=DEV)))
+        torch.cuda.empty_cache()
+        pos = (lens - 1).to(torch.int32)
+        wipe_last(layers, lens)
+        graph = c.step_graph(layers, wl.H, pos, lens, wl.N)
+        for _ in range(2):                      # a replay must give the same again
+            clear(layers)
+            graph.launch()
+            c.synchronize()
+            torch.cuda.synchronize()
+            for y, l in zip(layers, (0, wl.L - 1)):
+                out = y["out"].cpu().numpy()
+                idx, w = y["idx_out"].cpu().numpy(), y["w_out"].cpu().numpy()
+                for (b, h) in sample_units(wl, 6, seed=l):
+                    r = oracle_unit(wl, l, b, h, wl.N)
+                    check_unit(r, wl.N, out[b, h], idx[b, h], w[b, h],
+                               tag="graph config2 layer %d (%d,%d)" % (l, b, h))
+        c.device_check()
+        graph.close()
+    finally:
+        c.close()
