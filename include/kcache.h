@@ -47,7 +47,8 @@ typedef enum { KC_GATHER_ZEROCOPY = 0, KC_GATHER_STAGED = 1 } kc_gather_mode;
 typedef enum {
   KC_OK = 0,
   KC_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, H % Hkv != 0 ...     */
-  KC_ERR_UNSUPPORTED = -2, /* head_dim other than 128, group size not in {1,2,4,8}  */
+  KC_ERR_UNSUPPORTED = -2, /* head_dim other than 128, group size H/Hkv not a power
+                              of two up to 32                                       */
   KC_ERR_NOT_PINNED = -3,  /* v_host is not device-mapped host memory (or, with
                               v_in_hbm, not device memory)                           */
   KC_ERR_WORKSPACE = -4,   /* workspace could not be (re)allocated                   */
@@ -165,8 +166,10 @@ int kcache_prefill_store(kc_ctx* ctx, const kc_layer_cache* cache, const void* k
  * S~ = TopN(softmax(Q K^T / sqrt(d_h))) and A~ = S~ Part(V); section 3.3 for
  * the per-(sequence, head) granularity).
  *   q_dev         dev [B][H][d], cache dtype
- *   H             query heads; H % Hkv == 0 and H / Hkv in {1, 2, 4, 8}; query
- *                 head h reads KV head h / (H / Hkv)
+ *   H             query heads; H % Hkv == 0 and H / Hkv in {1, 2, 4, 8, 16, 32};
+ *                 query head h reads KV head h / (H / Hkv).  Up to 8 heads of a
+ *                 group are scored from one pass over the K rows; groups of 16 or
+ *                 32 take 2 or 4 passes
  *   seq_lens_dev  dev int32 [B], 1 <= s_b <= S_cap, counts the current token,
  *                 whose K and V rows the caller has already stored
  *   N             >= 1; N_eff = min(N, s_b) positions are kept

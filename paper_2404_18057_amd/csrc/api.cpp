@@ -352,8 +352,8 @@ int shape_status(const kc_layer_cache* cache, int32_t H, int32_t N, const char**
   if (H < 1 || N < 1) return *why = "H and N must be positive", KC_ERR_INVALID_ARG;
   if (H % cache->Hkv != 0) return *why = "H must be a multiple of Hkv", KC_ERR_INVALID_ARG;
   const int G = H / cache->Hkv;
-  if (G != 1 && G != 2 && G != 4 && G != 8)
-    return *why = "group size H/Hkv must be 1, 2, 4 or 8", KC_ERR_UNSUPPORTED;
+  if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16 && G != 32)
+    return *why = "group size H/Hkv must be 1, 2, 4, 8, 16 or 32", KC_ERR_UNSUPPORTED;
   if (!sizes_ok(cache->B, H, cache->S_cap, N)) return *why = "sizes too large", KC_ERR_INVALID_ARG;
   return KC_OK;
 }
@@ -372,11 +372,11 @@ struct FusedPlan {
   size_t bytes;
 };
 FusedPlan plan_fused(const kc_ctx* c, int B, int H, int Hkv, int S_cap, int N) {
-  const int G = H / Hkv;
+  const int split = kc::kv_split_for(H / Hkv), G = H / Hkv / split;  // per launch unit
   FusedPlan p;
   p.R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
             ? c->fused_rows
-            : kc::fused_rows_per_block(B * Hkv, G, S_cap, N);
+            : kc::fused_rows_per_block(B * Hkv * split, G, S_cap, N);
   p.chunks_cap = (S_cap + p.R - 1) / p.R;
   p.kk = std::min(N, p.R);
   p.bytes = fused_bytes((size_t)B * H, p.chunks_cap, p.kk, N);
@@ -408,19 +408,20 @@ int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, con
   a.w = w_out_dev ? w_out_dev : reinterpret_cast<float*>(p);
   a.counters = counters;
   a.flags = c->flags;
+  a.kv_split = kc::kv_split_for(H / Hkv);
   a.H = H;
-  a.Hkv = Hkv;
+  a.Hkv = Hkv * a.kv_split;
   a.S_cap = S_cap;
   a.N = N;
   a.R = pl.R;
   a.chunks_cap = pl.chunks_cap;
   a.kk = pl.kk;
   a.kv0 = 0;
-  a.kv_count = B * Hkv;
+  a.kv_count = B * a.Hkv;
   a.renorm = c->renorm;
   a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
   KernelTimer t(c, KC_KERNEL_FUSED, st);
-  KC_HIP(c, kc::launch_fused(a, cache->dtype, B * Hkv, st));
+  KC_HIP(c, kc::launch_fused(a, cache->dtype, a.kv_count, st));
   return KC_OK;
 }
 
@@ -429,11 +430,11 @@ struct FullPlan {
   size_t part_bytes, bytes;
 };
 FullPlan plan_full(const kc_ctx* c, int B, int H, int Hkv, int S_cap) {
-  const int G = H / Hkv;
+  const int split = kc::kv_split_for(H / Hkv), G = H / Hkv / split;  // per launch unit
   FullPlan p;
   p.R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
             ? c->fused_rows
-            : kc::full_rows_per_block(B * Hkv, G, S_cap);
+            : kc::full_rows_per_block(B * Hkv * split, G, S_cap);
   p.chunks_cap = (S_cap + p.R - 1) / p.R;
   const size_t units = (size_t)B * H;
   p.part_bytes = round256(units * p.chunks_cap * sizeof(float2));
@@ -454,12 +455,13 @@ int enqueue_full(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, cons
   a.part_o = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.part_bytes);
   a.counters = counters;
   a.flags = c->flags;
+  a.kv_split = kc::kv_split_for(H / cache->Hkv);
   a.H = H;
-  a.Hkv = cache->Hkv;
+  a.Hkv = cache->Hkv * a.kv_split;
   a.S_cap = cache->S_cap;
   a.R = pl.R;
   a.chunks_cap = pl.chunks_cap;
-  a.kv_count = cache->B * cache->Hkv;
+  a.kv_count = cache->B * a.Hkv;
   a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
   KernelTimer t(c, KC_KERNEL_FULL, st);
   KC_HIP(c, kc::launch_full(a, cache->dtype, st));
@@ -702,7 +704,8 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
   const size_t need = fused ? pl.bytes : unfused_bytes(units, S_cap, N);
   if ((rc = ensure_workspace(c, need)) != KC_OK) return rc;
   if (staged && (rc = ensure_staged(c, units * N)) != KC_OK) return rc;
-  if (fused && (rc = ensure_counters(c, kv_units)) != KC_OK) return rc;
+  if (fused && (rc = ensure_counters(c, (size_t)kv_units * kc::kv_split_for(G))) != KC_OK)
+    return rc;
 
   hipStream_t st = (hipStream_t)stream;
   const kc::Shape sh{B, H, Hkv, S_cap, N, cache->dtype, c->renorm};
@@ -847,7 +850,9 @@ int kcache_full_attention(kc_ctx* c, const kc_layer_cache* cache, const void* q_
 
   const FullPlan pl = plan_full(c, cache->B, H, cache->Hkv, cache->S_cap);
   if ((rc = ensure_workspace(c, pl.bytes)) != KC_OK) return rc;
-  if ((rc = ensure_counters(c, (size_t)cache->B * cache->Hkv)) != KC_OK) return rc;
+  if ((rc = ensure_counters(c, (size_t)cache->B * cache->Hkv *
+                                   kc::kv_split_for(H / cache->Hkv))) != KC_OK)
+    return rc;
 
   hipStream_t st = (hipStream_t)stream;
   if (c->have_last) KC_HIP(c, hipStreamWaitEvent(st, c->ev_last, 0));
@@ -896,7 +901,8 @@ int prepare_step(kc_ctx* c, const char* who, const kc_step_layer* layers, int32_
     need = std::max(need, y.cache.v_in_hbm
                               ? plan_full(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap).bytes
                               : plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N).bytes);
-    kv_max = std::max(kv_max, (size_t)y.cache.B * y.cache.Hkv);
+    kv_max = std::max(kv_max, (size_t)y.cache.B * y.cache.Hkv *
+                                  kc::kv_split_for(H / y.cache.Hkv));
   }
   *lane_bytes = round256(need);
   *lane_counters = (kv_max + 63) & ~(size_t)63;

@@ -124,7 +124,8 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const int ku_rel = xcd + kXcds * (in_xcd / a.chunks_cap);
   if (ku_rel >= a.kv_count) return;  // padding of the last group of eight units
   const int ku = a.kv0 + ku_rel;
-  const int b = ku / a.Hkv, hk = ku - b * a.Hkv;
+  const int b = ku / a.Hkv, hk = ku - b * a.Hkv;  // a.Hkv counts launch units per sequence
+  const size_t kv_phys = (size_t)b * (a.Hkv / a.kv_split) + hk / a.kv_split;
   const int R = a.R, N = a.N, kk = a.kk;
   int s = a.seq_lens[b];
   if (s < 1 || s > a.S_cap) {
@@ -151,7 +152,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   KC_T(t0);
 
   // ---------------- 1. scores of R positions for the G heads of the group -> LDS
-  score_chunk<DT, G, FT>(a.q + (size_t)unit0 * kHeadDim, a.K + (size_t)ku * a.S_cap * kHeadDim, a.S_cap,
+  score_chunk<DT, G, FT>(a.q + (size_t)unit0 * kHeadDim, a.K + kv_phys * a.S_cap * kHeadDim, a.S_cap,
                          s, row0, R, a.scale, sm.z);
   __syncthreads();
   KC_T(t1);
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const bool z_in_lds = M <= kFusedZFloats, pos_in_lds = 2 * M <= kFusedZFloats;
   const bool stage_out = n_eff <= kStage;
   const uint4* __restrict__ Vp =
-      reinterpret_cast<const uint4*>(a.V) + (size_t)ku * a.S_cap * 16;
+      reinterpret_cast<const uint4*>(a.V) + kv_phys * a.S_cap * 16;
 #pragma unroll 1
   for (int g = 0; g < G; ++g) {
     const int unit = unit0 + g;

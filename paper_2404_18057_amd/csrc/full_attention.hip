@@ -43,7 +43,8 @@ __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const int chunk = in_xcd % a.chunks_cap;
   const int ku = xcd + kXcds * (in_xcd / a.chunks_cap);
   if (ku >= a.kv_count) return;
-  const int b = ku / a.Hkv, hk = ku - b * a.Hkv;
+  const int b = ku / a.Hkv, hk = ku - b * a.Hkv;  // a.Hkv counts launch units per sequence
+  const size_t kv_phys = (size_t)b * (a.Hkv / a.kv_split) + hk / a.kv_split;
   const int R = a.R;
   int s = a.seq_lens[b];
   if (s < 1 || s > a.S_cap) {
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const int n = (s - row0 < R) ? s - row0 : R;
 
   // ---------------- 1. scores -> LDS
-  score_chunk<DT, G, AT>(a.q + (size_t)unit0 * kHeadDim, a.K + (size_t)ku * a.S_cap * kHeadDim,
+  score_chunk<DT, G, AT>(a.q + (size_t)unit0 * kHeadDim, a.K + kv_phys * a.S_cap * kHeadDim,
                          a.S_cap, s, row0, R, a.scale, sm.z);
   __syncthreads();
 
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     for (int i = 0; i < 8; ++i) acc[g][i] = 0.f;
   {
     const uint4* __restrict__ Vp =
-        reinterpret_cast<const uint4*>(a.V + (size_t)ku * a.S_cap * kHeadDim);
+        reinterpret_cast<const uint4*>(a.V + kv_phys * a.S_cap * kHeadDim);
     const int rows_per_wave = R / AW;
 #pragma unroll 1
     for (int it = 0; it < rows_per_wave / 64; ++it) {

@@ -25,6 +25,12 @@ __device__ __forceinline__ uint4 load_stream16(const uint4* p) {
 constexpr int kFlagBadSeqLen = 1;
 constexpr int kFlagBadPos = 2;
 
+// The kernels score at most 8 query heads from one pass over a K row.  Larger groups
+// (16 or 32 query heads per KV head) run as 2 or 4 launch units per KV head, each with 8 of
+// the group's heads: the launch then sees Hkv * split KV heads of group size 8, and unit
+// (b, hk') reads the rows of physical head hk' / split.
+inline int kv_split_for(int G) { return G > 8 ? G / 8 : 1; }
+
 struct Shape {
   int B, H, Hkv, S_cap, N, dtype;
   int renorm = 0;  // 1: kept weights are divided by their sum
@@ -75,6 +81,7 @@ struct FusedArgs {
   int kv0;
   int kv_count;    // KV units of this launch
   int renorm;      // 1: kept weights are divided by their sum
+  int kv_split;    // launch units per physical KV head (see kv_split_for)
   float scale;
 };
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N);
@@ -95,6 +102,7 @@ struct FullArgs {
   int R;           // positions per workgroup, a multiple of kFusedThreads, R * G <= kFusedZFloats
   int chunks_cap;  // ceil(S_cap / R)
   int kv_count;
+  int kv_split;    // launch units per physical KV head (see kv_split_for)
   float scale;
 };
 int full_rows_per_block(int kv_units, int G, int S_cap);

@@ -59,11 +59,13 @@ __global__ __launch_bounds__(256) void kscan_kernel(const uint16_t* __restrict__
                                                     const uint16_t* __restrict__ K,
                                                     const int32_t* __restrict__ seq_lens,
                                                     float* __restrict__ z, int H, int Hkv,
-                                                    int S_cap, int kv0, int chunks_per_unit,
-                                                    float scale, int* __restrict__ flags) {
+                                                    int kv_split, int S_cap, int kv0,
+                                                    int chunks_per_unit, float scale,
+                                                    int* __restrict__ flags) {
   const int chunk = blockIdx.x % chunks_per_unit;
   const int ku = kv0 + blockIdx.x / chunks_per_unit;
-  const int b = ku / Hkv, hk = ku - b * Hkv;
+  const int b = ku / Hkv, hk = ku - b * Hkv;  // Hkv counts launch units per sequence
+  const size_t kv_phys = (size_t)b * (Hkv / kv_split) + hk / kv_split;
   int s = seq_lens[b];
   if (s < 1 || s > S_cap) {
     if (threadIdx.x == 0 && chunk == 0) atomicOr(flags, kFlagBadSeqLen);
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(256) void kscan_kernel(const uint16_t* __restrict__
     qv[g] = *reinterpret_cast<const uint4*>(q + ((size_t)b * H + hk * G + g) * kHeadDim + sub * 8);
 
   const uint4* __restrict__ Kp =
-      reinterpret_cast<const uint4*>(K + (size_t)ku * S_cap * kHeadDim);
+      reinterpret_cast<const uint4*>(K + kv_phys * S_cap * kHeadDim);
   float* __restrict__ zu = z + ((size_t)b * H + hk * G) * S_cap;
 
   constexpr int kRowsPerWave = kScanRowsPerBlock / 4;
@@ -126,7 +128,11 @@ __global__ __launch_bounds__(256) void kscan_kernel(const uint16_t* __restrict__
 template <int DT>
 hipError_t launch_dt(const Shape& sh, const void* q, const void* k, const int32_t* seq_lens,
                      float* z, int kv0, int kv_count, int* flags, hipStream_t st) {
-  const int G = sh.H / sh.Hkv;
+  // groups of 16 or 32 query heads run as 2 or 4 launch units of 8 heads per KV head
+  const int split = kv_split_for(sh.H / sh.Hkv);
+  const int G = sh.H / sh.Hkv / split, Hkv_l = sh.Hkv * split;
+  kv0 *= split;
+  kv_count *= split;
   const int chunks = (sh.S_cap + kScanRowsPerBlock - 1) / kScanRowsPerBlock;
   const dim3 grid((unsigned)(kv_count * chunks)), block(256);
   const float scale = 0.08838834764831845f;  // 1 / sqrt(128)
@@ -134,7 +140,7 @@ hipError_t launch_dt(const Shape& sh, const void* q, const void* k, const int32_
   const uint16_t* kp = static_cast<const uint16_t*>(k);
 #define KC_LAUNCH(GG)                                                                          \
   hipLaunchKernelGGL((kscan_kernel<DT, GG>), grid, block, 0, st, qp, kp, seq_lens, z, sh.H,     \
-                     sh.Hkv, sh.S_cap, kv0, chunks, scale, flags)
+                     Hkv_l, split, sh.S_cap, kv0, chunks, scale, flags)
   switch (G) {
     case 1: KC_LAUNCH(1); break;
     case 2: KC_LAUNCH(2); break;

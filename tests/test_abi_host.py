@@ -36,6 +36,8 @@ def test_workspace_size_formula():
     ((16, 8, 8192, 128, 1, 32, 128), 0),      # GQA group of 4, bf16
     ((1, 8, 2048, 64, 0, 8, 64), -2),         # head_dim other than 128
     ((1, 8, 2048, 128, 0, 24, 64), -2),       # group of 3
+    ((1, 2, 2048, 128, 0, 32, 64), 0),        # 32 query heads over 2 KV groups: group of 16
+    ((1, 1, 2048, 128, 0, 64, 64), -2),       # group of 64
     ((1, 8, 2048, 128, 0, 12, 64), -1),       # H not a multiple of Hkv
     ((1, 8, 2048, 128, 2, 8, 64), -1),        # unknown dtype
     ((0, 8, 2048, 128, 0, 8, 64), -1),

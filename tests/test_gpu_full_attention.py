@@ -109,7 +109,7 @@ def test_config4_ragged_lengths(kc, ctx):
 
 # ------------------------------------------------------------------ edge cases
 @pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
-@pytest.mark.parametrize("G", [1, 2, 4, 8])
+@pytest.mark.parametrize("G", [1, 2, 4, 8, 16, 32])
 def test_group_sizes_and_ragged_tails(kc, ctx, dtype, G):
     rng = np.random.default_rng(40 + G)
     B, Hkv, S, d = 3, 2, 2500, 128

@@ -178,16 +178,18 @@ def test_small_shapes_and_ragged_tails(kc, ctx, S_cap, lens, N):
     check_manual(res, lens, N)
 
 
-@pytest.mark.parametrize("G", [2, 8])
+@pytest.mark.parametrize("G", [2, 8, 16, 32])
 def test_other_group_sizes(kc, ctx, G):
+    # 16 and 32 (e.g. 32 query heads over 2 KV groups, or multi-query attention) run as
+    # several launch units of 8 heads per KV head
     rng = np.random.default_rng(G)
-    B, Hkv, S, d, N = 2, 2, 777, 128, 20
+    B, Hkv, S, d, N = 2, 2, 1500, 128, 20
     H = Hkv * G
     q = rng.standard_normal((B, H, d))
     K = rng.standard_normal((B, Hkv, S, d))
     V = rng.standard_normal((B, Hkv, S, d))
-    res = manual_case(kc, ctx, q, K, V, [777, 400], N, dtype=torch.bfloat16)
-    check_manual(res, [777, 400], N, G=G)
+    res = manual_case(kc, ctx, q, K, V, [1500, 400], N, dtype=torch.bfloat16)
+    check_manual(res, [1500, 400], N, G=G)
 
 
 def test_staged_gather_matches_zero_copy(kc, ctx):
