@@ -40,6 +40,13 @@ def _load():
         lib.kcache_oracle_unit.restype = ctypes.c_int
         lib.kcache_oracle_unit_renormalised.argtypes = lib.kcache_oracle_unit.argtypes
         lib.kcache_oracle_unit_renormalised.restype = ctypes.c_int
+        lib.kcache_oracle_unit_k8.argtypes = [c_p, c_p, ctypes.c_int, c_p, ctypes.c_int, c_i32,
+                                              c_i32, c_i32, c_p, c_p, c_p, c_p, c_p]
+        lib.kcache_oracle_unit_k8.restype = ctypes.c_int
+        lib.kcache_oracle_e4m3_decode.argtypes = [c_p, c_i64, c_p]
+        lib.kcache_oracle_e4m3_decode.restype = None
+        lib.kcache_oracle_e4m3_quantise.argtypes = [c_p, c_i64, ctypes.c_int, ctypes.c_int, c_p]
+        lib.kcache_oracle_e4m3_quantise.restype = None
         lib.kcache_oracle_decode.argtypes = [c_p, c_p, c_p, ctypes.c_int, c_i32, c_i32, c_i32,
                                              c_i32, c_i32, c_p, c_i32, c_p, c_p, c_p, ctypes.c_int]
         lib.kcache_oracle_decode.restype = ctypes.c_int
@@ -51,6 +58,9 @@ def _load():
         lib.kcache_oracle_store.argtypes = [c_p, c_p, c_p, c_p, c_p, c_i32, c_i32, c_i32, c_i32,
                                             c_i32]
         lib.kcache_oracle_store.restype = ctypes.c_int
+        lib.kcache_oracle_store_k8.argtypes = [c_p, c_p, c_p, c_p, c_p, c_i32, c_i32, c_i32, c_i32,
+                                               c_i32, ctypes.c_int, ctypes.c_int]
+        lib.kcache_oracle_store_k8.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -72,6 +82,46 @@ def decode16(bits, dtype):
     out = np.empty(bits.shape, dtype=np.float64)
     _load().kcache_oracle_decode16(_ptr(bits), bits.size, dtype, _ptr(out))
     return out
+
+
+def e4m3_decode(codes):
+    """Exact double values of an array of OCP FP8 E4M3 codes (uint8)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    out = np.empty(codes.shape, np.float64)
+    _load().kcache_oracle_e4m3_decode(_ptr(codes), codes.size, _ptr(out))
+    return out
+
+
+def e4m3_quantise(bits, dtype, k_exp):
+    """E4M3 codes of the 16-bit values `bits` scaled by 2^-k_exp (nearest, ties to even,
+    saturating at 448)."""
+    bits = _u16(bits)
+    out = np.empty(bits.shape, np.uint8)
+    _load().kcache_oracle_e4m3_quantise(_ptr(bits), bits.size, dtype, int(k_exp), _ptr(out))
+    return out
+
+
+def decode_unit_k8(q, K8, k_exp, V, dtype, N, want_scores=False):
+    """decode_unit with the K rows given as E4M3 codes K8 [s][d] and the cache exponent."""
+    q, V = _u16(q), _u16(V)
+    K8 = np.ascontiguousarray(K8, dtype=np.uint8)
+    s, d = K8.shape
+    assert q.shape == (d,) and V.shape == (s, d)
+    out = np.empty(d, np.float64)
+    idx = np.empty(N, np.int32)
+    w = np.empty(N, np.float64)
+    z = np.empty(s, np.float64) if want_scores else None
+    p = np.empty(s, np.float64) if want_scores else None
+    rc = _load().kcache_oracle_unit_k8(_ptr(q), _ptr(K8), int(k_exp), _ptr(V), dtype, s, d, N,
+                                       _ptr(out), _ptr(idx), _ptr(w),
+                                       _ptr(z) if want_scores else None,
+                                       _ptr(p) if want_scores else None)
+    if rc != 0:
+        raise ValueError("kcache_oracle_unit_k8 rejected its arguments")
+    res = dict(out=out, idx=idx, w=w)
+    if want_scores:
+        res.update(z=z, p=p)
+    return res
 
 
 def decode_unit(q, K, V, dtype, N, want_scores=False, renormalise=False):
@@ -169,3 +219,22 @@ def store(k_cache, v_cache, k_new, v_new, pos):
                                      _ptr(pos), B, T, Hkv, S_cap, d)
     if rc != 0:
         raise ValueError("kcache_oracle_store rejected its arguments")
+
+
+def store_k8(k8_cache, v_cache, k_new, v_new, pos, dtype, k_exp):
+    """In-place store into a cache whose K rows are E4M3 codes (uint8) with exponent k_exp."""
+    if k8_cache.dtype != np.uint8 or v_cache.dtype != np.uint16:
+        raise TypeError("k8_cache must be uint8, v_cache uint16")
+    for a in (k8_cache, v_cache):
+        if not a.flags.c_contiguous or not a.flags.writeable:
+            raise TypeError("caches must be writable contiguous arrays")
+    k_new, v_new = _u16(k_new), _u16(v_new)
+    B, T, Hkv, d = k_new.shape
+    assert v_new.shape == k_new.shape and k8_cache.shape == v_cache.shape
+    assert k8_cache.shape[0] == B and k8_cache.shape[1] == Hkv and k8_cache.shape[3] == d
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    rc = _load().kcache_oracle_store_k8(_ptr(k8_cache), _ptr(v_cache), _ptr(k_new), _ptr(v_new),
+                                        _ptr(pos), B, T, Hkv, k8_cache.shape[2], d, dtype,
+                                        int(k_exp))
+    if rc != 0:
+        raise ValueError("kcache_oracle_store_k8 rejected its arguments")

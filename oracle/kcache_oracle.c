@@ -80,6 +80,63 @@ static double kco_decode(uint16_t bits, int dtype) {
   return dtype == KCO_BF16 ? kco_bf16_to_double(bits) : kco_half_to_double(bits);
 }
 
+/*
+ * 8-bit K storage (a variant outside the paper's own experiments; section 1 names
+ * cache quantisation as the other way to cut the bytes a decode step moves).  The
+ * code is OCP FP8 E4M3: 1 sign bit, 4 exponent bits with bias 7, 3 fraction bits,
+ * no infinities, S.1111.111 is NaN, largest finite value 448.  A K element is
+ * stored as code(k * 2^-e) for one integer e per cache and read back as
+ * value(code) * 2^e.  The power-of-two scale makes every step exact, so the stored
+ * byte is a pure function of the 16-bit input.
+ */
+static double kco_e4m3_to_double(uint8_t b) {
+  int sign = (b >> 7) & 1;
+  int expo = (b >> 3) & 0xf;
+  int frac = b & 7;
+  double v;
+  if (expo == 15 && frac == 7) {
+    v = NAN;
+  } else if (expo == 0) {
+    v = ldexp((double)frac, -9); /* subnormal: frac/8 * 2^-6 */
+  } else {
+    v = ldexp((double)(frac + 8), expo - 10); /* (1 + frac/8) * 2^(expo-7) */
+  }
+  return sign ? -v : v;
+}
+
+/* Nearest E4M3 code of x, ties to the even code, magnitudes above 448 saturate to
+ * 448, NaN gives the NaN code.  Zero keeps its sign. */
+static uint8_t kco_double_to_e4m3(double x) {
+  uint8_t sign = signbit(x) ? 0x80 : 0;
+  if (isnan(x)) return (uint8_t)(sign | 0x7f);
+  double a = fabs(x);
+  if (a >= 448.0) return (uint8_t)(sign | 0x7e);
+  if (a == 0.0) return sign;
+  int e;
+  (void)frexp(a, &e); /* a = f * 2^e with f in [0.5, 1): a lies in [2^(e-1), 2^e) */
+  int expo = e - 1;   /* floor(log2 a) */
+  if (expo < -6) expo = -6; /* subnormal codes share the spacing of the smallest normals */
+  /* spacing of the codes in this binade is 2^(expo-3); nearbyint rounds ties to even */
+  double n = nearbyint(ldexp(a, 3 - expo)); /* 8..16 for normals, 0..8 below 2^-6 */
+  double v = ldexp(n, expo - 3);            /* the rounded magnitude, exactly representable */
+  if (v == 0.0) return sign;
+  if (v < ldexp(1.0, -6)) return (uint8_t)(sign | (int)ldexp(v, 9)); /* subnormal: frac = v * 2^9 */
+  (void)frexp(v, &e);
+  int ve = e - 1;
+  int frac = (int)(ldexp(v, 3 - ve)) - 8;
+  return (uint8_t)(sign | ((ve + 7) << 3) | frac);
+}
+
+/* Exposed for the pins: decode of codes, and quantisation of 16-bit values k as
+ * code(k * 2^-k_exp). */
+void kcache_oracle_e4m3_decode(const uint8_t* codes, int64_t n, double* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = kco_e4m3_to_double(codes[i]);
+}
+void kcache_oracle_e4m3_quantise(const uint16_t* bits, int64_t n, int dtype, int k_exp,
+                                 uint8_t* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = kco_double_to_e4m3(ldexp(kco_decode(bits[i], dtype), -k_exp));
+}
+
 /* Exposed so the decode can be pinned against a library conversion. */
 void kcache_oracle_decode16(const uint16_t* bits, int64_t n, int dtype, double* out) {
   for (int64_t i = 0; i < n; ++i) out[i] = kco_decode(bits[i], dtype);
@@ -115,10 +172,13 @@ static int kco_cmp_i32(const void* a, const void* b) {
  *   p_out  [s]      optional (may be NULL): full softmax
  * Returns 0, or -1 on bad arguments / allocation failure.
  */
-static int kco_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, int dtype, int32_t s,
-                    int32_t d, int32_t N, int renormalise, double* out, int32_t* idx, double* w,
-                    double* z_out, double* p_out) {
-  if (!q || !K || !V || !out || !idx || !w || s < 1 || d < 1 || N < 1) return -1;
+/* K comes either as 16-bit values (K) or, when K8 is given, as E4M3 codes with the
+ * cache's exponent k_exp. */
+static int kco_unit(const uint16_t* q, const uint16_t* K, const uint8_t* K8, int k_exp,
+                    const uint16_t* V, int dtype, int32_t s, int32_t d, int32_t N,
+                    int renormalise, double* out, int32_t* idx, double* w, double* z_out,
+                    double* p_out) {
+  if (!q || (!K && !K8) || !V || !out || !idx || !w || s < 1 || d < 1 || N < 1) return -1;
   double* z = (double*)malloc(sizeof(double) * (size_t)s);
   double* p = (double*)malloc(sizeof(double) * (size_t)s);
   double* qd = (double*)malloc(sizeof(double) * (size_t)d);
@@ -133,8 +193,11 @@ static int kco_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, int
   const double inv_sqrt_d = 1.0 / sqrt((double)d);
   for (int32_t t = 0; t < s; ++t) {
     double acc = 0.0;
-    for (int32_t c = 0; c < d; ++c)
-      acc += qd[c] * kco_decode(K[(size_t)t * d + c], dtype);
+    for (int32_t c = 0; c < d; ++c) {
+      const double k = K8 ? ldexp(kco_e4m3_to_double(K8[(size_t)t * d + c]), k_exp)
+                          : kco_decode(K[(size_t)t * d + c], dtype);
+      acc += qd[c] * k;
+    }
     z[t] = acc * inv_sqrt_d;
   }
 
@@ -185,7 +248,7 @@ static int kco_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, int
 int kcache_oracle_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, int dtype,
                        int32_t s, int32_t d, int32_t N, double* out, int32_t* idx, double* w,
                        double* z_out, double* p_out) {
-  return kco_unit(q, K, V, dtype, s, d, N, 0, out, idx, w, z_out, p_out);
+  return kco_unit(q, K, NULL, 0, V, dtype, s, d, N, 0, out, idx, w, z_out, p_out);
 }
 
 /*
@@ -198,7 +261,14 @@ int kcache_oracle_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, 
 int kcache_oracle_unit_renormalised(const uint16_t* q, const uint16_t* K, const uint16_t* V,
                                     int dtype, int32_t s, int32_t d, int32_t N, double* out,
                                     int32_t* idx, double* w, double* z_out, double* p_out) {
-  return kco_unit(q, K, V, dtype, s, d, N, 1, out, idx, w, z_out, p_out);
+  return kco_unit(q, K, NULL, 0, V, dtype, s, d, N, 1, out, idx, w, z_out, p_out);
+}
+
+/* The unit with its K rows stored as E4M3 codes K8 [s][d] and the exponent k_exp. */
+int kcache_oracle_unit_k8(const uint16_t* q, const uint8_t* K8, int k_exp, const uint16_t* V,
+                          int dtype, int32_t s, int32_t d, int32_t N, double* out, int32_t* idx,
+                          double* w, double* z_out, double* p_out) {
+  return kco_unit(q, NULL, K8, k_exp, V, dtype, s, d, N, 0, out, idx, w, z_out, p_out);
 }
 
 /*
@@ -327,6 +397,30 @@ int kcache_oracle_store(uint16_t* k_cache, uint16_t* v_cache, const uint16_t* k_
           size_t src = (((size_t)b * T + t) * Hkv + hk) * d + c;
           size_t dst = (((size_t)b * Hkv + hk) * S_cap + (size_t)(pos[b] + t)) * d + c;
           k_cache[dst] = k_new[src];
+          v_cache[dst] = v_new[src];
+        }
+  return 0;
+}
+
+/*
+ * The same store for a cache whose K rows are kept as E4M3 codes with exponent
+ * k_exp (see kco_double_to_e4m3): K rows are quantised on the way in, V rows are
+ * copied unchanged.  k8_cache [B][Hkv][S_cap][d] bytes.
+ */
+int kcache_oracle_store_k8(uint8_t* k8_cache, uint16_t* v_cache, const uint16_t* k_new,
+                           const uint16_t* v_new, const int32_t* pos, int32_t B, int32_t T,
+                           int32_t Hkv, int32_t S_cap, int32_t d, int dtype, int k_exp) {
+  if (!k8_cache || !v_cache || !k_new || !v_new || !pos) return -1;
+  if (B < 1 || T < 1 || Hkv < 1 || S_cap < 1 || d < 1) return -1;
+  for (int32_t b = 0; b < B; ++b)
+    if (pos[b] < 0 || (int64_t)pos[b] + T > S_cap) return -1;
+  for (int32_t b = 0; b < B; ++b)
+    for (int32_t t = 0; t < T; ++t)
+      for (int32_t hk = 0; hk < Hkv; ++hk)
+        for (int32_t c = 0; c < d; ++c) {
+          size_t src = (((size_t)b * T + t) * Hkv + hk) * d + c;
+          size_t dst = (((size_t)b * Hkv + hk) * S_cap + (size_t)(pos[b] + t)) * d + c;
+          k8_cache[dst] = kco_double_to_e4m3(ldexp(kco_decode(k_new[src], dtype), -k_exp));
           v_cache[dst] = v_new[src];
         }
   return 0;

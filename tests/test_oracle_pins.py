@@ -458,3 +458,100 @@ def test_renormalised_variant_is_the_literal_one_rescaled_and_full_attention_at_
     full = oracle.full_unit(q, K, V, BF16)
     assert np.allclose(oracle.decode_unit(q, K, V, BF16, 120, renormalise=True)["out"], full,
                        rtol=1e-12, atol=1e-14)
+
+
+# ---------------------------------------------------------------- 8-bit K storage (E4M3)
+def e4m3_table():
+    """Values of the 256 OCP E4M3 codes from the format's definition, written independently
+    of the oracle: (-1)^s * 2^(e-7) * (1 + m/8), subnormals 2^-6 * m/8, S.1111.111 = NaN."""
+    vals = np.empty(256)
+    for c in range(256):
+        s_, e, m = c >> 7, (c >> 3) & 15, c & 7
+        if e == 15 and m == 7:
+            v = np.nan
+        elif e == 0:
+            v = 2.0 ** -6 * m / 8
+        else:
+            v = 2.0 ** (e - 7) * (1 + m / 8)
+        vals[c] = -v if s_ else v
+    return vals
+
+
+def test_e4m3_decode_matches_the_format_definition_and_torch():
+    codes = np.arange(256, dtype=np.uint8)
+    got = oracle.e4m3_decode(codes)
+    want = e4m3_table()
+    nan = np.isnan(want)
+    assert (np.isnan(got) == nan).all() and nan.sum() == 2
+    assert (got[~nan] == want[~nan]).all()
+    assert np.nanmax(got) == 448.0 and got[0x08] == 2.0 ** -6 and got[0x01] == 2.0 ** -9
+    if hasattr(torch, "float8_e4m3fn"):      # library decode of the same format
+        lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+        assert (lib[~nan] == got[~nan]).all() and np.isnan(lib[nan]).all()
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("k_exp", [0, -3, 2])
+def test_e4m3_quantise_is_nearest_ties_to_even_saturating_by_brute_force(dtype, k_exp):
+    # every 16-bit input against an exhaustive search over the 254 finite codes
+    allbits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    x = back(allbits, dtype) * 2.0 ** -k_exp
+    got = oracle.e4m3_quantise(allbits, dtype, k_exp)
+    table = e4m3_table()
+    finite = ~np.isnan(x)
+    pos_codes = np.arange(0, 0x7f)                        # non-negative finite codes
+    pos_vals = table[pos_codes]
+    a = np.abs(x[finite])
+    a_sat = np.minimum(a, 448.0)                          # saturation
+    dist = np.abs(a_sat[:, None] - pos_vals[None, :])
+    best = dist.min(axis=1)
+    is_best = dist == best[:, None]
+    # ties: the even code (its last fraction bit is 0)
+    even = (pos_codes % 2 == 0)[None, :]
+    pick = np.where((is_best & even).any(axis=1), (is_best & even).argmax(axis=1),
+                    is_best.argmax(axis=1))
+    want = pos_codes[pick].astype(np.uint8) | np.where(np.signbit(x[finite]), 0x80, 0).astype(np.uint8)
+    assert (got[finite] == want).all()
+    assert ((got[~finite] & 0x7f) == 0x7f).all()          # NaN stays NaN
+    # representable values are fixed points
+    vals = oracle.e4m3_decode(got[finite])
+    assert (np.abs(vals) <= 448).all()
+
+
+def test_k8_unit_is_the_16_bit_unit_on_the_dequantised_rows():
+    # when every K value is representable in E4M3 (times 2^e) the two routines must agree
+    rng = np.random.default_rng(98)
+    s, d, N, e = 90, 32, 11, -2
+    codes = rng.integers(0, 0x7f, size=(s, d)).astype(np.uint8) | \
+        (rng.integers(0, 2, size=(s, d)).astype(np.uint8) << 7)
+    codes[(codes & 0x7f) == 0x7f] = 0x30
+    Kf = e4m3_table()[codes] * 2.0 ** e
+    Kf = np.clip(Kf, -60000, 60000)
+    codes = oracle.e4m3_quantise(bits(Kf), F16, e)        # round trip through fp16 (exact here)
+    Kf = oracle.e4m3_decode(codes) * 2.0 ** e
+    q = bits(rng.standard_normal(d) * 0.3)
+    V = bits(rng.standard_normal((s, d)))
+    a = oracle.decode_unit_k8(q, codes, e, V, F16, N, want_scores=True)
+    b = oracle.decode_unit(q, bits(Kf), V, F16, N, want_scores=True)
+    assert (back(bits(Kf)) == Kf).all()
+    assert np.array_equal(a["idx"], b["idx"])
+    assert np.allclose(a["z"], b["z"], rtol=1e-13, atol=1e-13)
+    assert np.allclose(a["out"], b["out"], rtol=1e-12, atol=1e-14)
+
+
+def test_store_k8_is_store_followed_by_quantisation():
+    rng = np.random.default_rng(99)
+    B, T, Hkv, d, S_cap, e = 2, 5, 3, 16, 12, -1
+    k_new = bits(rng.standard_normal((B, T, Hkv, d)) * 3)
+    v_new = bits(rng.standard_normal((B, T, Hkv, d)))
+    pos = np.array([0, 7], np.int32)
+    k8 = np.full((B, Hkv, S_cap, d), 0x55, np.uint8)
+    v = np.zeros((B, Hkv, S_cap, d), np.uint16)
+    oracle.store_k8(k8, v, k_new, v_new, pos, F16, e)
+    k16 = np.full((B, Hkv, S_cap, d), 0xFFFF, np.uint16)   # NaN pattern marks untouched rows
+    v2 = np.zeros_like(v)
+    oracle.store(k16, v2, k_new, v_new, pos)
+    touched = k16 != 0xFFFF
+    assert np.array_equal(v, v2)
+    assert np.array_equal(k8[touched], oracle.e4m3_quantise(k16[touched], F16, e))
+    assert (k8[~touched] == 0x55).all()
