@@ -29,6 +29,7 @@ sys.path.insert(0, ROOT)
 import kcache_inputs as ki  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
+K_FP8_EXP = -5   # cache exponent of the 8-bit K variant: covers |K| < 14 of the synthetic workloads
 
 
 def parse():
@@ -63,6 +64,9 @@ def parse():
                     help="the first L layers keep their V cache in HBM and run conventional "
                          "attention (the method's second knob, section 3.1 / Table 2); -1 = every "
                          "layer, i.e. the conventional KV-cache baseline")
+    ap.add_argument("--k-fp8", action="store_true",
+                    help="variant: 8-bit K cache (E4M3 codes, cache exponent -5); halves the bytes "
+                         "of the K scan")
     ap.add_argument("--crossover", action="store_true",
                     help="also time, on one layer of this workload's shape, the KCache launch "
                          "against conventional attention with V in HBM over a grid of context "
@@ -109,17 +113,17 @@ def main():
     layer_elems = int(np.prod(shape))
     v_all = torch.empty(max(L - Lh, 1) * layer_elems, dtype=dt, pin_memory=True)
     for layer in range(L):
-        k_cache = torch.empty(shape, dtype=dt, device=dev)
+        k_cache = torch.empty(shape, dtype=torch.uint8 if a.k_fp8 else dt, device=dev)
         if layer < Lh:
             v_cache = torch.empty(shape, dtype=dt, device=dev)
         else:
             v_cache = v_all[(layer - Lh) * layer_elems:(layer - Lh + 1) * layer_elems].view(shape)
-        cache = kc.LayerCache(k_cache, v_cache)
+        cache = kc.LayerCache(k_cache, v_cache, k_exp=K_FP8_EXP)
         kt = torch.empty((wl.B, 1, wl.Hkv, wl.d), dtype=dt, device=dev)
         vt = torch.empty((wl.B, 1, wl.Hkv, wl.d), dtype=dt, device=dev)
         for b in range(wl.B):
             k, v = ki.gen_kv_units(wl, layer, b, hks, wl.S_cap, dev)
-            sub = kc.LayerCache(k_cache[b:b + 1], v_cache[b:b + 1])
+            sub = kc.LayerCache(k_cache[b:b + 1], v_cache[b:b + 1], k_exp=K_FP8_EXP)
             zero = torch.zeros(1, dtype=torch.int32, device=dev)
             alive = []   # the V half runs on the library's side stream: inputs must outlive it
             for t in range(0, wl.S_cap, T_chunk):
@@ -215,7 +219,7 @@ def main():
     ctx.device_check()
 
     units_per_layer = wl.B * wl.H
-    k_bytes_layer = int(lens.astype(np.int64).sum()) * wl.Hkv * wl.d * 2
+    k_bytes_layer = int(lens.astype(np.int64).sum()) * wl.Hkv * wl.d * (1 if a.k_fp8 else 2)
     n_eff = np.minimum(lens, wl.N).astype(np.int64)
     v_bytes_layer = int(n_eff.sum()) * wl.H * wl.d * 2
     fused_path = prof["fused"][1] > 0 or Lh == L
@@ -254,7 +258,7 @@ def main():
         tj = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
         path = "conventional" if Lh == L else "fused" if fused_path else "unfused"
         ent = tj.get("%s/%s" % (wl.name, path))
-        if ent and L == wl.L and Lh in (0, L):
+        if ent and L == wl.L and Lh in (0, L) and not a.k_fp8:
             traffic = ent["fetch_bytes_per_launch"] + ent["write_bytes_per_launch"]
     except (OSError, ValueError, KeyError):
         traffic = None
@@ -290,9 +294,10 @@ def main():
         "config": {"workload": wl.name, "layers": L, "batch": wl.B, "q_heads": wl.H,
                    "kv_heads": wl.Hkv, "head_dim": wl.d, "context": int(lens.max()), "top_n": wl.N,
                    "gather": a.gather, "path": "fused" if fused_path else "unfused",
+                   "k_cache": "e4m3, exponent %d" % K_FP8_EXP if a.k_fp8 else wl.dtype,
                    "pipeline_parts": a.parts, "v_in_hbm_layers": Lh, "step_mode": step_mode,
                    "lanes": a.lanes,
-                   "k_cache_GiB": L * np.prod(shape) * 2 / 2 ** 30, "setup_s": round(setup_s, 1)},
+                   "k_cache_GiB": L * np.prod(shape) * (1 if a.k_fp8 else 2) / 2 ** 30, "setup_s": round(setup_s, 1)},
         "roofline": roofline,
         "v_gather": {
             "kernel": "fused_kernel (whole launch)" if fused_path else "gather_kernel",
@@ -322,7 +327,8 @@ def main():
         result["crossover"] = crossover_leg(ctx, kc, wl, caches[-1], qs[-1], dev, probes)
 
     if not a.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, L, Lh, a.cpu_units, a.cpu_passes, outs, idxs, ws)
+        result["cpu_baseline"] = cpu_baseline(wl, L, Lh, a.cpu_units, a.cpu_passes, outs, idxs, ws,
+                                              a.k_fp8)
     print(json.dumps(result))
 
 
@@ -413,7 +419,7 @@ def crossover_leg(ctx, kc, wl, cache, q, dev, probes, reps=10):
             "eq4_ratio_with_overlap": (hbm / link / 2) if hbm and link else None}
 
 
-def cpu_baseline(wl, L, Lh, n_units, passes, outs, idxs, ws):
+def cpu_baseline(wl, L, Lh, n_units, passes, outs, idxs, ws, k_fp8=False):
     """The CPU oracle, as it stands, on a seeded sample of this workload's units,
     one thread per available core; its results double as a spot check of the GPU
     outputs of the last timed step."""
@@ -458,8 +464,13 @@ def cpu_baseline(wl, L, Lh, n_units, passes, outs, idxs, ws):
             else:
                 failures.append("%s: conventional attention max err %g" % ((l, b, h), err.max()))
             continue
-        r = oracle.decode_unit(q[i, 0], K[i, 0, :sl[i]], V[i, 0, :sl[i]], code, wl.N,
-                               want_scores=True)
+        if k_fp8:
+            codes = oracle.e4m3_quantise(K[i, 0, :sl[i]], code, K_FP8_EXP)
+            r = oracle.decode_unit_k8(q[i, 0], codes, K_FP8_EXP, V[i, 0, :sl[i]], code, wl.N,
+                                      want_scores=True)
+        else:
+            r = oracle.decode_unit(q[i, 0], K[i, 0, :sl[i]], V[i, 0, :sl[i]], code, wl.N,
+                                   want_scores=True)
         r["v"] = oracle.decode16(V[i, 0, :sl[i]], code)
         try:
             identical += check_unit(r, wl.N, outs[l][b, h].cpu().numpy(),

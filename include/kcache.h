@@ -72,6 +72,16 @@ typedef struct {
   int32_t v_in_hbm; /* 0: V in CPU memory (the method's default placement);
                        1: this layer keeps its V cache in HBM (section 3.1 and the
                        caption of Table 2: the first L layers)                      */
+  int32_t k_fp8;    /* 0: K rows are `dtype` values, 256 bytes each;
+                       1: variant with an 8-bit K cache (section 1 names cache
+                       quantisation as the other way to cut the bytes a decode step
+                       moves): k_dev holds OCP FP8 E4M3 codes, 128 bytes per row,
+                       element = value(code) * 2^k_exp.  kcache_prefill_store
+                       quantises the 16-bit rows it is given (nearest, ties to even,
+                       saturating at 448).  Needs dtype KC_F16; served by the fused
+                       zero-copy decode path only                                   */
+  int32_t k_exp;    /* the cache's power-of-two scale exponent, |k_exp| <= 32; used
+                       only with k_fp8                                              */
 } kc_layer_cache;
 
 /* Identifiers for kcache_profile_read. */

@@ -27,7 +27,8 @@ class KCacheError(RuntimeError):
 
 class _CLayerCache(ctypes.Structure):
     _fields_ = [("k_dev", _c_p), ("v_host", _c_p), ("B", _c_i32), ("Hkv", _c_i32),
-                ("S_cap", _c_i32), ("d", _c_i32), ("dtype", _c_i32), ("v_in_hbm", _c_i32)]
+                ("S_cap", _c_i32), ("d", _c_i32), ("dtype", _c_i32), ("v_in_hbm", _c_i32),
+                ("k_fp8", _c_i32), ("k_exp", _c_i32)]
 
 
 class _CStepLayer(ctypes.Structure):
@@ -108,8 +109,11 @@ class LayerCache:
     fp16 or bf16.  The V cache is a pinned host tensor, or a device tensor for a
     layer that keeps V in HBM.  Holds references, owns nothing else."""
 
-    def __init__(self, k_dev, v):
-        if k_dev.dtype != v.dtype or k_dev.shape != v.shape or k_dev.dim() != 4:
+    def __init__(self, k_dev, v, k_exp=0):
+        """A uint8 k_dev is an 8-bit K cache of E4M3 codes with the scale exponent k_exp."""
+        self.k_fp8 = k_dev.dtype == torch.uint8
+        if k_dev.shape != v.shape or k_dev.dim() != 4 or \
+                (k_dev.dtype != v.dtype and not self.k_fp8):
             raise ValueError("K and V caches must have the same 4-d shape and dtype")
         if not (k_dev.is_contiguous() and v.is_contiguous()):
             raise ValueError("caches must be contiguous")
@@ -119,7 +123,8 @@ class LayerCache:
         self.v_in_hbm = bool(v.is_cuda)
         B, Hkv, S_cap, d = k_dev.shape
         self.c = _CLayerCache(k_dev.data_ptr(), v.data_ptr(), B, Hkv, S_cap, d,
-                              _dtype_code(k_dev.dtype), 1 if self.v_in_hbm else 0)
+                              _dtype_code(v.dtype), 1 if self.v_in_hbm else 0,
+                              1 if self.k_fp8 else 0, int(k_exp) if self.k_fp8 else 0)
 
 
 class StepGraph:
@@ -154,7 +159,7 @@ def _dtype_code(dt):
 
 def check_shapes(B, Hkv, S_cap, d, dtype_code, H, N):
     """Host-only shape validation (no GPU needed); returns the kc_status."""
-    c = _CLayerCache(None, None, B, Hkv, S_cap, d, dtype_code, 0)
+    c = _CLayerCache(None, None, B, Hkv, S_cap, d, dtype_code, 0, 0, 0)
     return int(lib().kcache_check_shapes(ctypes.byref(c), H, N))
 
 
@@ -214,7 +219,7 @@ class Context:
         B, T, Hkv, d = k_new.shape
         if v_new.shape != k_new.shape or (B, Hkv, d) != (cache.c.B, cache.c.Hkv, cache.c.d):
             raise ValueError("k_new / v_new shape does not match the cache")
-        if k_new.dtype != cache.k.dtype or v_new.dtype != cache.k.dtype:
+        if k_new.dtype != cache.v.dtype or v_new.dtype != cache.v.dtype:
             raise ValueError("k_new / v_new dtype does not match the cache")
         if not (k_new.is_contiguous() and v_new.is_contiguous() and pos.is_contiguous()):
             raise ValueError("inputs must be contiguous")
@@ -234,7 +239,7 @@ class Context:
                          gather_mode=GATHER_ZEROCOPY, stream=None):
         """q: device [B][H][d]; seq_lens: device int32 [B].  Returns out fp32 [B][H][d]."""
         B, H, d = q.shape
-        if (B, d) != (cache.c.B, cache.c.d) or q.dtype != cache.k.dtype or not q.is_contiguous():
+        if (B, d) != (cache.c.B, cache.c.d) or q.dtype != cache.v.dtype or not q.is_contiguous():
             raise ValueError("q does not match the cache")
         if seq_lens.dtype != torch.int32 or seq_lens.numel() != B or not seq_lens.is_cuda:
             raise ValueError("seq_lens must be a device int32 [B] tensor")
@@ -256,7 +261,7 @@ class Context:
     def full_attention(self, cache, q, seq_lens, out=None, stream=None):
         """Conventional attention of a layer whose V cache is in HBM.  Returns out fp32 [B][H][d]."""
         B, H, d = q.shape
-        if (B, d) != (cache.c.B, cache.c.d) or q.dtype != cache.k.dtype or not q.is_contiguous():
+        if (B, d) != (cache.c.B, cache.c.d) or q.dtype != cache.v.dtype or not q.is_contiguous():
             raise ValueError("q does not match the cache")
         if seq_lens.dtype != torch.int32 or seq_lens.numel() != B or not seq_lens.is_cuda:
             raise ValueError("seq_lens must be a device int32 [B] tensor")

@@ -345,6 +345,12 @@ int shape_status(const kc_layer_cache* cache, int32_t H, int32_t N, const char**
     return *why = "dtype must be KC_F16 or KC_BF16", KC_ERR_INVALID_ARG;
   if (cache->v_in_hbm != 0 && cache->v_in_hbm != 1)
     return *why = "v_in_hbm must be 0 or 1", KC_ERR_INVALID_ARG;
+  if (cache->k_fp8 != 0 && cache->k_fp8 != 1)
+    return *why = "k_fp8 must be 0 or 1", KC_ERR_INVALID_ARG;
+  if (cache->k_fp8 && (cache->k_exp < -32 || cache->k_exp > 32))
+    return *why = "k_exp must be in [-32, 32]", KC_ERR_INVALID_ARG;
+  if (cache->k_fp8 && cache->dtype != KC_F16)
+    return *why = "an 8-bit K cache needs dtype KC_F16", KC_ERR_UNSUPPORTED;
   if (cache->d != kc::kHeadDim) return *why = "head dimension must be 128", KC_ERR_UNSUPPORTED;
   if ((int64_t)cache->B * cache->Hkv * cache->S_cap >= (1ll << 40))
     return *why = "cache too large", KC_ERR_INVALID_ARG;
@@ -371,12 +377,13 @@ struct FusedPlan {
   int R, chunks_cap, kk;
   size_t bytes;
 };
-FusedPlan plan_fused(const kc_ctx* c, int B, int H, int Hkv, int S_cap, int N) {
+FusedPlan plan_fused(const kc_ctx* c, int B, int H, int Hkv, int S_cap, int N, int k_fp8) {
   const int split = kc::kv_split_for(H / Hkv), G = H / Hkv / split;  // per launch unit
   FusedPlan p;
   p.R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
             ? c->fused_rows
-            : kc::fused_rows_per_block(B * Hkv * split, G, S_cap, N);
+            : kc::fused_rows_per_block(B * Hkv * split, G, S_cap, N,
+                                       k_fp8 ? kc::kRowBytes / 2 : kc::kRowBytes);
   p.chunks_cap = (S_cap + p.R - 1) / p.R;
   p.kk = std::min(N, p.R);
   p.bytes = fused_bytes((size_t)B * H, p.chunks_cap, p.kk, N);
@@ -419,7 +426,9 @@ int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, con
   a.kv0 = 0;
   a.kv_count = B * a.Hkv;
   a.renorm = c->renorm;
-  a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
+  a.k_fp8 = cache->k_fp8;
+  // 1 / sqrt(128), times the cache's 2^k_exp for an 8-bit K cache
+  a.scale = cache->k_fp8 ? ldexpf(0.08838834764831845f, cache->k_exp) : 0.08838834764831845f;
   KernelTimer t(c, KC_KERNEL_FUSED, st);
   KC_HIP(c, kc::launch_fused(a, cache->dtype, a.kv_count, st));
   return KC_OK;
@@ -639,7 +648,7 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
     {
       KernelTimer t(c, KC_KERNEL_STORE_K, st);
       KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, v_new_dev, v_map, pos_dev, T,
-                                 c->flags, 0, st));
+                                 c->flags, 0, st, cache->k_fp8, cache->k_exp));
     }
     if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, st));
     return KC_OK;
@@ -650,7 +659,7 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
     {
       KernelTimer t(c, KC_KERNEL_STORE_K, st);
       KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, v_new_dev, v_map, pos_dev, T,
-                                 c->flags, 1, st));
+                                 c->flags, 1, st, cache->k_fp8, cache->k_exp));
     }
     if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, st));
     return KC_OK;
@@ -669,7 +678,7 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
   {
     KernelTimer t(c, KC_KERNEL_STORE_K, st);
     KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, nullptr, nullptr, pos_dev, T,
-                               c->flags, 0, st));
+                               c->flags, 0, st, cache->k_fp8, cache->k_exp));
   }
   return KC_OK;
 }
@@ -689,6 +698,9 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
                 gather_mode);
   DeviceGuard g(c->device);
   if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  if (cache->k_fp8 && (gather_mode == KC_GATHER_STAGED || !c->fused))
+    return fail(c, KC_ERR_UNSUPPORTED, "kcache_decode_attention: an 8-bit K cache is served by "
+                "the fused zero-copy path only");
   if (cache->v_in_hbm && gather_mode == KC_GATHER_STAGED)
     return fail(c, KC_ERR_UNSUPPORTED, "kcache_decode_attention: the staged gather needs the V "
                 "cache in host memory");
@@ -700,7 +712,7 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
   const int kv_units = B * Hkv;
   const bool staged = gather_mode == KC_GATHER_STAGED;
   const bool fused = !staged && c->fused;
-  const FusedPlan pl = plan_fused(c, B, H, Hkv, S_cap, N);
+  const FusedPlan pl = plan_fused(c, B, H, Hkv, S_cap, N, cache->k_fp8);
   const size_t need = fused ? pl.bytes : unfused_bytes(units, S_cap, N);
   if ((rc = ensure_workspace(c, need)) != KC_OK) return rc;
   if (staged && (rc = ensure_staged(c, units * N)) != KC_OK) return rc;
@@ -840,6 +852,8 @@ int kcache_full_attention(kc_ctx* c, const kc_layer_cache* cache, const void* q_
   if (rc != KC_OK) return fail(c, rc, "kcache_full_attention: %s", why);
   if (!cache->k_dev || !cache->v_host || !q_dev || !seq_lens_dev || !out_dev)
     return fail(c, KC_ERR_INVALID_ARG, "kcache_full_attention: NULL pointer argument");
+  if (cache->k_fp8)
+    return fail(c, KC_ERR_UNSUPPORTED, "kcache_full_attention: 8-bit K caches are not supported");
   if (!cache->v_in_hbm)
     return fail(c, KC_ERR_INVALID_ARG, "kcache_full_attention: this layer's V cache is in host "
                 "memory (v_in_hbm is 0); use kcache_decode_attention");
@@ -897,10 +911,14 @@ int prepare_step(kc_ctx* c, const char* who, const kc_step_layer* layers, int32_
                   "given or both be NULL", who, l);
     if (y.cache.B != layers[0].cache.B)
       return fail(c, KC_ERR_INVALID_ARG, "%s: layer %d: B differs from layer 0", who, l);
+    if (y.cache.k_fp8 && y.cache.v_in_hbm)
+      return fail(c, KC_ERR_UNSUPPORTED, "%s: layer %d: 8-bit K caches are not supported by "
+                  "conventional attention", who, l);
     if ((rc = v_pointer(c, &y.cache, &(*v_maps)[l])) != KC_OK) return rc;
     need = std::max(need, y.cache.v_in_hbm
                               ? plan_full(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap).bytes
-                              : plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N).bytes);
+                              : plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N,
+                                           y.cache.k_fp8).bytes);
     kv_max = std::max(kv_max, (size_t)y.cache.B * y.cache.Hkv *
                                   kc::kv_split_for(H / y.cache.Hkv));
   }
@@ -933,7 +951,8 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
       const kc::Shape sh{y.cache.B, 0, y.cache.Hkv, y.cache.S_cap, 0, y.cache.dtype};
       KernelTimer t(c, KC_KERNEL_STORE_K, s);
       KC_HIP(c, kc::launch_store(sh, y.k_new_dev, y.cache.k_dev, y.v_new_dev, v_maps[l], pos_dev, 1,
-                                 c->flags, y.cache.v_in_hbm ? 0 : 1, s));
+                                 c->flags, y.cache.v_in_hbm ? 0 : 1, s, y.cache.k_fp8,
+                                 y.cache.k_exp));
     }
     int rc;
     if (y.cache.v_in_hbm) {
@@ -941,7 +960,8 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
       rc = enqueue_full(c, &y.cache, v_maps[l], y.q_dev, H, seq_lens_dev, y.out_dev, pl, ws,
                         counters, s);
     } else {
-      const FusedPlan pl = plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N);
+      const FusedPlan pl =
+          plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N, y.cache.k_fp8);
       rc = enqueue_fused(c, &y.cache, v_maps[l], y.q_dev, H, seq_lens_dev, N, y.out_dev,
                          y.idx_out_dev, y.w_out_dev, pl, ws, counters, s);
     }

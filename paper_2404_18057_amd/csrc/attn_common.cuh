@@ -134,6 +134,86 @@ __device__ __forceinline__ void score_chunk(const uint16_t* __restrict__ q_group
   }
 }
 
+// ---- K rows stored as OCP FP8 E4M3 codes (1 sign, 4 exponent bits with bias 7, 3
+// fraction bits), 128 bytes per row.
+//
+// gfx950 converts two codes to two fp16 values in one instruction
+// (v_cvt_scalef32_pk_f16_fp8; with a scale of 1 the result is value(code) exactly, checked
+// for all finite codes on the hardware), which then go through the same packed dot product
+// as a 16-bit K row.
+
+// dot product of 4 E4M3 codes (one dword) with 4 fp16 values (qa: channels 0-1, qb: 2-3)
+__device__ __forceinline__ float dot4_e4m3(uint32_t w, uint32_t qa, uint32_t qb, float acc) {
+  const half2_t k01 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false);  // bytes 0, 1
+  const half2_t k23 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true);   // bytes 2, 3
+  acc = __builtin_amdgcn_fdot2(k01, __builtin_bit_cast(half2_t, qa), acc, false);
+  return __builtin_amdgcn_fdot2(k23, __builtin_bit_cast(half2_t, qb), acc, false);
+}
+
+// Sum over the 8 lanes of half a DPP row, returned to every lane of the half row.
+__device__ __forceinline__ float row8_sum(float x) {
+  x = dpp_add<0xB1>(x);   // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);   // quad_perm [2,3,0,1]
+  x = dpp_add<0x141>(x);  // row_half_mirror
+  return x;
+}
+
+// score_chunk for a K cache of E4M3 codes and fp16 queries.  A row is 8 lanes x 16 bytes,
+// a wave-wide 16-byte load reads 8 rows; 8 loads (64 rows) are in flight per wave.  `scale`
+// must carry 2^k_exp / sqrt(d_h).
+template <int G, int NT>
+__device__ __forceinline__ void score_chunk8(const uint16_t* __restrict__ q_group,
+                                             const uint8_t* __restrict__ K_unit, int S_cap, int s,
+                                             int row0, int R, float scale, float* z) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane & 7, rg = lane >> 3;
+  uint4 qv[G][2];  // this lane's 16 channels of every head
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const uint4* qp = reinterpret_cast<const uint4*>(q_group + (size_t)g * kHeadDim + sub * 16);
+    qv[g][0] = qp[0];
+    qv[g][1] = qp[1];
+  }
+  const uint4* __restrict__ Kp = reinterpret_cast<const uint4*>(K_unit);  // 8 per row
+  const int rows_per_wave = R / (NT / 64);  // a multiple of 64
+#pragma unroll 1
+  for (int it = 0; it < rows_per_wave / 64; ++it) {
+    const int local = wave * rows_per_wave + it * 64;
+    const int base = row0 + local;
+    if (base >= s) break;
+    uint4 kr[8];
+    if (base + 64 <= S_cap) {
+      const uint4* p = Kp + (size_t)(base + rg) * 8 + sub;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) kr[u] = load_stream16(p + u * 64);
+    } else {  // last rows of the cache: never read beyond S_cap
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        int r = base + u * 8 + rg;
+        r = r < S_cap ? r : S_cap - 1;
+        kr[u] = Kp[(size_t)r * 8 + sub];
+      }
+    }
+    float keep[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) keep[g] = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float x = dot4_e4m3(kr[u].x, qv[g][0].x, qv[g][0].y, 0.f);
+        x = dot4_e4m3(kr[u].y, qv[g][0].z, qv[g][0].w, x);
+        x = dot4_e4m3(kr[u].z, qv[g][1].x, qv[g][1].y, x);
+        x = dot4_e4m3(kr[u].w, qv[g][1].z, qv[g][1].w, x);
+        x = row8_sum(x);
+        keep[g] = (sub == u) ? x : keep[g];
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) z[g * R + local + sub * 8 + rg] = keep[g] * scale;
+  }
+}
+
 constexpr int kXcds = 8;  // accelerator complex dies of an MI355X
 
 }  // namespace kc

@@ -107,7 +107,7 @@ __device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp
 // would allow: measured on MI355X the launch is 3-7 % faster that way on the
 // large workloads (fewer units in flight per XCD, so units complete and start
 // pulling V earlier, and less contention for the CU while a workgroup selects).
-template <int DT, int G>
+template <int DT, int G, bool K8>
 __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void fused_kernel(
     FusedArgs a) {
   __shared__ Smem sm;
@@ -152,8 +152,13 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   KC_T(t0);
 
   // ---------------- 1. scores of R positions for the G heads of the group -> LDS
-  score_chunk<DT, G, FT>(a.q + (size_t)unit0 * kHeadDim, a.K + kv_phys * a.S_cap * kHeadDim, a.S_cap,
-                         s, row0, R, a.scale, sm.z);
+  if constexpr (K8)  // K rows are E4M3 codes, 128 bytes each
+    score_chunk8<G, FT>(a.q + (size_t)unit0 * kHeadDim,
+                        reinterpret_cast<const uint8_t*>(a.K) + kv_phys * a.S_cap * kHeadDim,
+                        a.S_cap, s, row0, R, a.scale, sm.z);
+  else
+    score_chunk<DT, G, FT>(a.q + (size_t)unit0 * kHeadDim, a.K + kv_phys * a.S_cap * kHeadDim,
+                           a.S_cap, s, row0, R, a.scale, sm.z);
   __syncthreads();
   KC_T(t1);
   KC_TADD(0, t1 - t0);
@@ -338,17 +343,17 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   }
 }
 
-template <int DT>
+template <int DT, bool K8>
 hipError_t launch_dt(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
   // eight XCDs each get ceil(kv_count / 8) units' worth of blocks
   const long long per_xcd = (long long)((kv_count + kXcds - 1) / kXcds) * a.chunks_cap;
   if (per_xcd * kXcds > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(per_xcd * kXcds)), block(FT);
   switch (G) {
-    case 1: hipLaunchKernelGGL((fused_kernel<DT, 1>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((fused_kernel<DT, 2>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((fused_kernel<DT, 4>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((fused_kernel<DT, 8>), grid, block, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((fused_kernel<DT, 1, K8>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((fused_kernel<DT, 2, K8>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((fused_kernel<DT, 4, K8>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((fused_kernel<DT, 8, K8>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -359,12 +364,14 @@ hipError_t launch_dt(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
 // Positions per workgroup.  Smaller chunks let units finish (and start pulling V)
 // earlier and more evenly, and leave fewer units in flight when the scan ends;
 // larger chunks mean fewer workgroups paying the fixed selection and hand-over
-// cost, and fewer candidates to merge.  Measured on MI355X, 1024 is the sweet spot
+// cost, and fewer candidates to merge.  Measured on MI355X, 256 KiB of K per workgroup
+// (1024 rows of 16-bit values, 2048 rows of 8-bit codes) is the sweet spot
 // as long as all of a unit's candidates fit the merging workgroup's LDS buffer,
 // ceil(S/R) * min(N, R) <= kFusedZFloats; otherwise the smallest R that fits.
-int fused_rows_per_block(int kv_units, int G, int S_cap, int N) {
+int fused_rows_per_block(int kv_units, int G, int S_cap, int N, int k_row_bytes) {
   const int cap = kFusedZFloats / G;
-  int R = 1024;
+  // the same K bytes per workgroup whatever the row size: an 8-bit K cache takes 2048 rows
+  int R = 1024 * (kRowBytes / k_row_bytes);
   while (R < cap && (int64_t)((S_cap + R - 1) / R) * (N < R ? N : R) > kFusedZFloats) R *= 2;
   if (R > cap) R = cap;
   // small problems: more, smaller workgroups as long as the merge still fits
@@ -378,7 +385,9 @@ hipError_t launch_fused(const FusedArgs& a, int dtype, int kv_count, hipStream_t
   if (kv_count <= 0) return hipSuccess;
   const int G = a.H / a.Hkv;
   if (a.R % kFusedThreads != 0 || a.R * G > kFusedZFloats) return hipErrorInvalidValue;
-  return dtype == 0 ? launch_dt<0>(a, G, kv_count, st) : launch_dt<1>(a, G, kv_count, st);
+  if (a.k_fp8) return dtype == 0 ? launch_dt<0, true>(a, G, kv_count, st) : hipErrorInvalidValue;
+  return dtype == 0 ? launch_dt<0, false>(a, G, kv_count, st)
+                    : launch_dt<1, false>(a, G, kv_count, st);
 }
 
 }  // namespace kc

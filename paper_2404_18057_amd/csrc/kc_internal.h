@@ -56,8 +56,11 @@ hipError_t launch_gather(const Shape& sh, const void* v, const int32_t* idx, con
 
 // Copy rows of src [B][T][Hkv][d] to dst [B][Hkv][S_cap][d] at pos[b] + t; src2 / dst2
 // (may be null) are a second pair moved in the same launch.
+// With k_fp8 the first pair is quantised on the way: fp16 rows in, E4M3 codes of
+// value * 2^-k_exp out (128 bytes per row).
 hipError_t launch_store(const Shape& sh, const void* src, void* dst, const void* src2, void* dst2,
-                        const int32_t* pos, int T, int* flags, int dst_is_host, hipStream_t st);
+                        const int32_t* pos, int T, int* flags, int dst_is_host, hipStream_t st,
+                        int k_fp8 = 0, int k_exp = 0);
 
 // Fused decode kernel (decode_fused.hip): scan + local top-N per chunk, merge,
 // V pull and weighted sum in one launch.
@@ -82,9 +85,10 @@ struct FusedArgs {
   int kv_count;    // KV units of this launch
   int renorm;      // 1: kept weights are divided by their sum
   int kv_split;    // launch units per physical KV head (see kv_split_for)
+  int k_fp8;       // 1: K rows are E4M3 codes (128 bytes per row); scale carries 2^k_exp
   float scale;
 };
-int fused_rows_per_block(int kv_units, int G, int S_cap, int N);
+int fused_rows_per_block(int kv_units, int G, int S_cap, int N, int k_row_bytes);
 hipError_t launch_fused(const FusedArgs& a, int dtype, int kv_count, hipStream_t st);
 
 // Conventional attention with K and V in HBM (full_attention.hip).

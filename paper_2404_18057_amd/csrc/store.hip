@@ -30,6 +30,45 @@ constexpr int kHeadTile = 16;  // KV heads per workgroup, four per pass
 //
 // src2 / dst2, when not null, are a second tensor pair moved with the same
 // indices (the K and V rows of a decode-step append in one launch).
+//
+// K8: the first pair is quantised on the way, fp16 values in, OCP FP8 E4M3 codes of
+// value * 2^-k_exp out (nearest, ties to even, saturating at 448; the power-of-two scale
+// keeps every step exact).  A destination row is then 16 lanes x 8 bytes.
+
+// E4M3 code of x: 1 sign, 4 exponent bits (bias 7), 3 fraction bits, no infinities.
+__device__ __forceinline__ uint32_t quant_e4m3(float x) {
+  const uint32_t u = __float_as_uint(x), sign = (u >> 24) & 0x80u, a = u & 0x7fffffffu;
+  uint32_t code;
+  if (a > 0x7f800000u) {
+    code = 0x7fu;  // NaN
+  } else if (a >= 0x43e00000u) {
+    code = 0x7eu;  // |x| >= 448: the largest finite value
+  } else if (a < 0x3c800000u) {
+    // below 2^-6 the codes are 2^-9 apart (subnormals; 8 is the smallest normal's code)
+    code = (uint32_t)__float2int_rn(__uint_as_float(a) * 512.f);
+  } else {
+    // round the 23 fraction bits to 3, ties to even; a carry moves into the exponent
+    const uint32_t r = (a + 0x7ffffu + ((a >> 20) & 1u)) >> 20;
+    code = r - (120u << 3);  // exponent bias 127 -> 7
+  }
+  return sign | code;
+}
+
+__device__ __forceinline__ uint2 quant_row8(const uint4& v, int k_exp) {
+  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  uint32_t c[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const half2_t h = __builtin_bit_cast(half2_t, w[i]);
+    c[2 * i] = quant_e4m3(ldexpf((float)h.x, -k_exp));
+    c[2 * i + 1] = quant_e4m3(ldexpf((float)h.y, -k_exp));
+  }
+  return make_uint2(c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24),
+                    c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24));
+}
+
+template <bool K8>
 __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ src,
                                                     uint4* __restrict__ dst,
                                                     const uint4* __restrict__ src2,
@@ -37,7 +76,7 @@ __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ sr
                                                     const int32_t* __restrict__ pos, int B, int T,
                                                     int Hkv, int S_cap, int t_tiles, int h_tiles,
                                                     unsigned total_tiles,
-                                                    int* __restrict__ flags) {
+                                                    int* __restrict__ flags, int k_exp) {
   const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
   const int ti = grp >> 2, hi = grp & 3;
   for (unsigned tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
@@ -63,7 +102,12 @@ __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ sr
     for (int i = 0; i < 4; ++i) {
       const int hk = (int)ht * kHeadTile + i * 4 + hi;
       const size_t to = (((size_t)b * Hkv + hk) * S_cap + (size_t)p) * 16 + sub;
-      if (ok[i]) dst[to] = v[i];
+      if (ok[i]) {
+        if constexpr (K8)
+          reinterpret_cast<uint2*>(dst)[to] = quant_row8(v[i], k_exp);
+        else
+          dst[to] = v[i];
+      }
       if (ok[i] && src2) dst2[to] = v2[i];
     }
   }
@@ -72,7 +116,8 @@ __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ sr
 }  // namespace
 
 hipError_t launch_store(const Shape& sh, const void* src, void* dst, const void* src2, void* dst2,
-                        const int32_t* pos, int T, int* flags, int dst_is_host, hipStream_t st) {
+                        const int32_t* pos, int T, int* flags, int dst_is_host, hipStream_t st,
+                        int k_fp8, int k_exp) {
   if (sh.B <= 0 || T <= 0 || sh.Hkv <= 0) return hipSuccess;
   const long long t_tiles = (T + kTokTile - 1) / kTokTile;
   const long long h_tiles = (sh.Hkv + kHeadTile - 1) / kHeadTile;
@@ -81,10 +126,17 @@ hipError_t launch_store(const Shape& sh, const void* src, void* dst, const void*
   long long blocks = tiles;
   const long long cap = dst_is_host ? kHostStoreBlocks : 0x7fffffffLL;
   if (blocks > cap) blocks = cap;
-  hipLaunchKernelGGL(store_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                     static_cast<const uint4*>(src), static_cast<uint4*>(dst),
-                     static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,
-                     sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags);
+  if (k_fp8)
+    hipLaunchKernelGGL(store_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st,
+                       static_cast<const uint4*>(src), static_cast<uint4*>(dst),
+                       static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,
+                       sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags,
+                       k_exp);
+  else
+    hipLaunchKernelGGL(store_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st,
+                       static_cast<const uint4*>(src), static_cast<uint4*>(dst),
+                       static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,
+                       sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags, 0);
   return hipGetLastError();
 }
 
