@@ -282,34 +282,38 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 
     int32_t* iu = a.idx + (size_t)unit * N;
     float* wu = a.w + (size_t)unit * N;
-    // Candidate positions that did not fit in LDS are fetched after the selection,
-    // all kept entries at once: emit() then records the candidate's index instead.
+    // With room in the LDS staging arrays (N_eff <= kStage) the selection writes nothing to
+    // global memory: weights and positions are collected in LDS and written out afterwards
+    // in whole lines, and candidate positions that did not fit in LDS beside the scores are
+    // fetched then, all kept entries in one round trip.
     const bool pos_later = !pos_in_lds && stage_out;
     float kept = 0.f;  // this thread's share of the kept softmax mass (renormalised variant)
     auto emit = [&](int r, int i, float v) {
       const float w = expf(v - mx) * inv_Z;
       kept += w;
-      wu[r] = w;
-      if (stage_out) stage_f[r] = w;
-      if (pos_later) {
-        stage_i[r] = i;
+      if (stage_out) {
+        stage_f[r] = w;
+        stage_i[r] = pos_in_lds ? pos_l[i] : i;
       } else {
-        const int32_t t = pos_in_lds ? pos_l[i] : ld_dev(cp + i);
-        iu[r] = t;
-        if (stage_out) stage_i[r] = t;
+        wu[r] = w;
+        iu[r] = pos_in_lds ? pos_l[i] : ld_dev(cp + i);
       }
     };
     if (z_in_lds)
       block_topn<FT, true>([&](int i) { return sm.z[i]; }, M, n_eff, &sm.sc, emit);
     else  // more candidates than the LDS buffer holds: read them around the L2 every pass
       block_topn<FT, true>([&](int i) { return ld_dev(cz + i); }, M, n_eff, &sm.sc, emit);
-    if (pos_later) {
+    if (stage_out) {
       for (int r = tid; r < n_eff; r += FT) {
-        const int32_t t = ld_dev(cp + stage_i[r]);
-        stage_i[r] = t;
+        int32_t t = stage_i[r];
+        if (pos_later) {
+          t = ld_dev(cp + t);
+          stage_i[r] = t;
+        }
         iu[r] = t;
+        if (!a.renorm) wu[r] = stage_f[r];
       }
-      __syncthreads();
+      if (pos_later) __syncthreads();
     }
     if (a.renorm) {
       // variant: divide the kept weights by their sum (equal maxima make the merge a sum)
