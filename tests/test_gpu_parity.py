@@ -367,3 +367,32 @@ def test_renormalised_variant_matches_its_oracle(kc, ctx, gather_mode):
     # and the default is untouched afterwards: kept weights sum to less than one again
     out, idx, w, _ = manual_case(kc, ctx, q, K, V, lens, 40)
     assert float(w[0, 0].sum()) < 0.999
+
+
+# ------------------------------------------------------------------ seeded random shapes
+@pytest.mark.parametrize("case", range(12))
+def test_seeded_random_shapes(kc, ctx, case):
+    """Shapes drawn from a seeded stream: batch, KV heads, group size, capacity, ragged
+    lengths (including 1 and the full capacity), N from 1 to beyond the longest sequence,
+    both dtypes, with a few duplicated K rows so that exact ties occur."""
+    rng = np.random.default_rng(1000 + case)
+    B = int(rng.integers(1, 4))
+    Hkv = int(rng.integers(1, 4))
+    G = int(rng.choice([1, 2, 4, 8, 16]))
+    S = int(rng.choice([1, 63, 512, 513, 1500, 2048, 4097, 6000]))
+    N = int(rng.choice([1, 2, 17, 64, 300, 1025, 2000]))
+    dtype = torch.float16 if rng.integers(2) else torch.bfloat16
+    H = Hkv * G
+    lens = [int(rng.integers(1, S + 1)) for _ in range(B)]
+    lens[0] = S
+    if B > 1:
+        lens[1] = 1
+    q = rng.standard_normal((B, H, 128))
+    K = rng.standard_normal((B, Hkv, S, 128))
+    V = rng.standard_normal((B, Hkv, S, 128))
+    if S >= 64:                      # exact ties: some rows repeat an earlier row
+        for _ in range(8):
+            a_, b_ = sorted(int(x) for x in rng.integers(0, S, size=2))
+            K[:, :, b_] = K[:, :, a_]
+    res = manual_case(kc, ctx, q, K, V, lens, N, dtype=dtype)
+    check_manual(res, lens, N, G=G)
