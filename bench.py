@@ -37,7 +37,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload of BASELINE.json (1-5)")
+    ap.add_argument("--config", type=int, default=2, help="workload of BASELINE.json (1-5); 6 = the shape of the paper's Table 4 "
+                         "headline row (batch 5, 16k context, N 128), for context")
     ap.add_argument("--layers", type=int, default=0, help="debug: use fewer layers (invalid as a result)")
     ap.add_argument("--parts", type=int, default=0, help="pipeline parts per layer (0 = library default)")
     ap.add_argument("--gather", choices=["zerocopy", "staged"], default="zerocopy")

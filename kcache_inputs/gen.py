@@ -70,6 +70,10 @@ CONFIGS = {
                 pivot_frac=0.01, seed=1004, len_range=(1024, 16384)),
     5: Workload("config5_llama2_13b_b2_s65536", L=40, B=2, H=40, Hkv=40, S_cap=65536, N=512,
                 dtype="f16", pivot_frac=0.005, seed=1005),
+    # not one of the five named workloads: the shape of the paper's headline row (Table 4:
+    # LLaMA2-7B, 15k prompt + 1k output, batch 5, N = 128), for context only
+    6: Workload("table4_llama2_7b_b5_s16384_n128", L=32, B=5, H=32, Hkv=32, S_cap=16384, N=128,
+                dtype="f16", pivot_frac=0.005, seed=1006),
 }
 
 
