@@ -107,9 +107,10 @@ typedef enum {
   KC_OPT_FUSED = 3,          /* 1 (default): KC_GATHER_ZEROCOPY decodes run as one fused
                                 launch per layer whose scores never leave the chip;
                                 0: separate scan / select / gather launches            */
-  KC_OPT_FUSED_ROWS = 4,     /* positions scored per workgroup of the fused launch: a
-                                multiple of 512 with rows * (H/Hkv) <= 8192, or 0 =
-                                choose from the shape (default)                        */
+  KC_OPT_FUSED_ROWS = 4,     /* positions scored per workgroup of the fused launch and
+                                of kcache_full_attention: a multiple of 512 with rows *
+                                min(H/Hkv, 8) <= 8192 (ignored otherwise), or 0 = choose
+                                from the shape (default)                               */
   KC_OPT_RENORMALIZE = 6,    /* 0 (default): the kept weights are the full-context softmax
                                 values, as Table 1 writes them; 1: variant that divides
                                 the N kept weights by their sum (section 4 remarks that
@@ -133,8 +134,10 @@ int kcache_create(kc_ctx** out, int device, size_t workspace_bytes_hint);
 /* Wait for the context's side streams, free its workspace.  NULL is accepted. */
 int kcache_destroy(kc_ctx* ctx);
 
-/* Bytes of device workspace a decode call of this shape needs (fp32 scores
- * [B][H][S_cap] plus index / weight buffers [B][H][N]).  0 on invalid sizes. */
+/* Upper bound of the device workspace one decode call of this shape needs on any
+ * path (the largest is the unfused one: fp32 scores [B][H][S_cap] plus index /
+ * weight buffers [B][H][N]); a step with L lanes needs that many times the fused
+ * path's share.  A hint for kcache_create; 0 on invalid sizes. */
 size_t kcache_workspace_bytes(int32_t B, int32_t H, int32_t S_cap, int32_t N);
 
 /* Text of the last error recorded in this context ("" if none).  The pointer
