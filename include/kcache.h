@@ -78,8 +78,8 @@ typedef struct {
                        moves): k_dev holds OCP FP8 E4M3 codes, 128 bytes per row,
                        element = value(code) * 2^k_exp.  kcache_prefill_store
                        quantises the 16-bit rows it is given (nearest, ties to even,
-                       saturating at 448).  Needs dtype KC_F16; served by the fused
-                       zero-copy decode path only                                   */
+                       saturating at 448).  Served by the fused zero-copy decode
+                       path only                                                   */
   int32_t k_exp;    /* the cache's power-of-two scale exponent, |k_exp| <= 32; used
                        only with k_fp8                                              */
 } kc_layer_cache;

@@ -349,8 +349,6 @@ int shape_status(const kc_layer_cache* cache, int32_t H, int32_t N, const char**
     return *why = "k_fp8 must be 0 or 1", KC_ERR_INVALID_ARG;
   if (cache->k_fp8 && (cache->k_exp < -32 || cache->k_exp > 32))
     return *why = "k_exp must be in [-32, 32]", KC_ERR_INVALID_ARG;
-  if (cache->k_fp8 && cache->dtype != KC_F16)
-    return *why = "an 8-bit K cache needs dtype KC_F16", KC_ERR_UNSUPPORTED;
   if (cache->d != kc::kHeadDim) return *why = "head dimension must be 128", KC_ERR_UNSUPPORTED;
   if ((int64_t)cache->B * cache->Hkv * cache->S_cap >= (1ll << 40))
     return *why = "cache too large", KC_ERR_INVALID_ARG;

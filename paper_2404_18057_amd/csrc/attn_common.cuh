@@ -142,12 +142,27 @@ __device__ __forceinline__ void score_chunk(const uint16_t* __restrict__ q_group
 // for all finite codes on the hardware), which then go through the same packed dot product
 // as a 16-bit K row.
 
-// dot product of 4 E4M3 codes (one dword) with 4 fp16 values (qa: channels 0-1, qb: 2-3)
+// dot product of 4 E4M3 codes (one dword) with 4 16-bit values (qa: channels 0-1, qb: 2-3)
+template <int DT>
 __device__ __forceinline__ float dot4_e4m3(uint32_t w, uint32_t qa, uint32_t qb, float acc) {
-  const half2_t k01 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false);  // bytes 0, 1
-  const half2_t k23 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true);   // bytes 2, 3
-  acc = __builtin_amdgcn_fdot2(k01, __builtin_bit_cast(half2_t, qa), acc, false);
-  return __builtin_amdgcn_fdot2(k23, __builtin_bit_cast(half2_t, qb), acc, false);
+  if constexpr (DT == 0) {
+    const half2_t k01 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false);  // bytes 0, 1
+    const half2_t k23 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true);   // bytes 2, 3
+    acc = __builtin_amdgcn_fdot2(k01, __builtin_bit_cast(half2_t, qa), acc, false);
+    return __builtin_amdgcn_fdot2(k23, __builtin_bit_cast(half2_t, qb), acc, false);
+  } else {
+    // bf16 queries: codes to fp32 (v_cvt_pk_f32_fp8, exact), whose upper halves are the
+    // same values as bf16 (a code has 3 fraction bits), packed two to a register
+    typedef float float2_t __attribute__((ext_vector_type(2)));
+    const float2_t f01 = __builtin_amdgcn_cvt_pk_f32_fp8(w, false);
+    const float2_t f23 = __builtin_amdgcn_cvt_pk_f32_fp8(w, true);
+    const uint32_t k01 = __builtin_amdgcn_perm(__float_as_uint(f01.y), __float_as_uint(f01.x),
+                                               0x07060302u);  // (hi16(y) << 16) | hi16(x)
+    const uint32_t k23 = __builtin_amdgcn_perm(__float_as_uint(f23.y), __float_as_uint(f23.x),
+                                               0x07060302u);
+    acc = dot2<1>(k01, qa, acc);
+    return dot2<1>(k23, qb, acc);
+  }
 }
 
 // Sum over the 8 lanes of half a DPP row, returned to every lane of the half row.
@@ -158,10 +173,10 @@ __device__ __forceinline__ float row8_sum(float x) {
   return x;
 }
 
-// score_chunk for a K cache of E4M3 codes and fp16 queries.  A row is 8 lanes x 16 bytes,
+// score_chunk for a K cache of E4M3 codes.  A row is 8 lanes x 16 bytes,
 // a wave-wide 16-byte load reads 8 rows; 8 loads (64 rows) are in flight per wave.  `scale`
 // must carry 2^k_exp / sqrt(d_h).
-template <int G, int NT>
+template <int DT, int G, int NT>
 __device__ __forceinline__ void score_chunk8(const uint16_t* __restrict__ q_group,
                                              const uint8_t* __restrict__ K_unit, int S_cap, int s,
                                              int row0, int R, float scale, float* z) {
@@ -201,10 +216,10 @@ __device__ __forceinline__ void score_chunk8(const uint16_t* __restrict__ q_grou
     for (int u = 0; u < 8; ++u) {
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float x = dot4_e4m3(kr[u].x, qv[g][0].x, qv[g][0].y, 0.f);
-        x = dot4_e4m3(kr[u].y, qv[g][0].z, qv[g][0].w, x);
-        x = dot4_e4m3(kr[u].z, qv[g][1].x, qv[g][1].y, x);
-        x = dot4_e4m3(kr[u].w, qv[g][1].z, qv[g][1].w, x);
+        float x = dot4_e4m3<DT>(kr[u].x, qv[g][0].x, qv[g][0].y, 0.f);
+        x = dot4_e4m3<DT>(kr[u].y, qv[g][0].z, qv[g][0].w, x);
+        x = dot4_e4m3<DT>(kr[u].z, qv[g][1].x, qv[g][1].y, x);
+        x = dot4_e4m3<DT>(kr[u].w, qv[g][1].z, qv[g][1].w, x);
         x = row8_sum(x);
         keep[g] = (sub == u) ? x : keep[g];
       }

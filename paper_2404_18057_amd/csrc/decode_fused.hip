@@ -153,7 +153,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 
   // ---------------- 1. scores of R positions for the G heads of the group -> LDS
   if constexpr (K8)  // K rows are E4M3 codes, 128 bytes each
-    score_chunk8<G, FT>(a.q + (size_t)unit0 * kHeadDim,
+    score_chunk8<DT, G, FT>(a.q + (size_t)unit0 * kHeadDim,
                         reinterpret_cast<const uint8_t*>(a.K) + kv_phys * a.S_cap * kHeadDim,
                         a.S_cap, s, row0, R, a.scale, sm.z);
   else
@@ -389,7 +389,9 @@ hipError_t launch_fused(const FusedArgs& a, int dtype, int kv_count, hipStream_t
   if (kv_count <= 0) return hipSuccess;
   const int G = a.H / a.Hkv;
   if (a.R % kFusedThreads != 0 || a.R * G > kFusedZFloats) return hipErrorInvalidValue;
-  if (a.k_fp8) return dtype == 0 ? launch_dt<0, true>(a, G, kv_count, st) : hipErrorInvalidValue;
+  if (a.k_fp8)
+    return dtype == 0 ? launch_dt<0, true>(a, G, kv_count, st)
+                      : launch_dt<1, true>(a, G, kv_count, st);
   return dtype == 0 ? launch_dt<0, false>(a, G, kv_count, st)
                     : launch_dt<1, false>(a, G, kv_count, st);
 }

@@ -56,7 +56,7 @@ hipError_t launch_gather(const Shape& sh, const void* v, const int32_t* idx, con
 
 // Copy rows of src [B][T][Hkv][d] to dst [B][Hkv][S_cap][d] at pos[b] + t; src2 / dst2
 // (may be null) are a second pair moved in the same launch.
-// With k_fp8 the first pair is quantised on the way: fp16 rows in, E4M3 codes of
+// With k_fp8 the first pair is quantised on the way: 16-bit rows in, E4M3 codes of
 // value * 2^-k_exp out (128 bytes per row).
 hipError_t launch_store(const Shape& sh, const void* src, void* dst, const void* src2, void* dst2,
                         const int32_t* pos, int T, int* flags, int dst_is_host, hipStream_t st,

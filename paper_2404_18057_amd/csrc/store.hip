@@ -31,7 +31,7 @@ constexpr int kHeadTile = 16;  // KV heads per workgroup, four per pass
 // src2 / dst2, when not null, are a second tensor pair moved with the same
 // indices (the K and V rows of a decode-step append in one launch).
 //
-// K8: the first pair is quantised on the way, fp16 values in, OCP FP8 E4M3 codes of
+// K8: the first pair is quantised on the way, 16-bit values in, OCP FP8 E4M3 codes of
 // value * 2^-k_exp out (nearest, ties to even, saturating at 448; the power-of-two scale
 // keeps every step exact).  A destination row is then 16 lanes x 8 bytes.
 
@@ -54,21 +54,31 @@ __device__ __forceinline__ uint32_t quant_e4m3(float x) {
   return sign | code;
 }
 
+template <int DT>
 __device__ __forceinline__ uint2 quant_row8(const uint4& v, int k_exp) {
   typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};
   uint32_t c[8];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const half2_t h = __builtin_bit_cast(half2_t, w[i]);
-    c[2 * i] = quant_e4m3(ldexpf((float)h.x, -k_exp));
-    c[2 * i + 1] = quant_e4m3(ldexpf((float)h.y, -k_exp));
+    float lo, hi;
+    if constexpr (DT == 0) {
+      const half2_t h = __builtin_bit_cast(half2_t, w[i]);
+      lo = (float)h.x;
+      hi = (float)h.y;
+    } else {
+      lo = __uint_as_float(w[i] << 16);
+      hi = __uint_as_float(w[i] & 0xffff0000u);
+    }
+    c[2 * i] = quant_e4m3(ldexpf(lo, -k_exp));
+    c[2 * i + 1] = quant_e4m3(ldexpf(hi, -k_exp));
   }
   return make_uint2(c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24),
                     c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24));
 }
 
-template <bool K8>
+// K8: 0 = plain copy, 1 = quantise fp16 rows, 2 = quantise bf16 rows
+template <int K8>
 __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ src,
                                                     uint4* __restrict__ dst,
                                                     const uint4* __restrict__ src2,
@@ -103,8 +113,8 @@ __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ sr
       const int hk = (int)ht * kHeadTile + i * 4 + hi;
       const size_t to = (((size_t)b * Hkv + hk) * S_cap + (size_t)p) * 16 + sub;
       if (ok[i]) {
-        if constexpr (K8)
-          reinterpret_cast<uint2*>(dst)[to] = quant_row8(v[i], k_exp);
+        if constexpr (K8 != 0)
+          reinterpret_cast<uint2*>(dst)[to] = quant_row8<K8 - 1>(v[i], k_exp);
         else
           dst[to] = v[i];
       }
@@ -126,14 +136,20 @@ hipError_t launch_store(const Shape& sh, const void* src, void* dst, const void*
   long long blocks = tiles;
   const long long cap = dst_is_host ? kHostStoreBlocks : 0x7fffffffLL;
   if (blocks > cap) blocks = cap;
-  if (k_fp8)
-    hipLaunchKernelGGL(store_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st,
+  if (k_fp8 && sh.dtype == 0)
+    hipLaunchKernelGGL(store_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, st,
+                       static_cast<const uint4*>(src), static_cast<uint4*>(dst),
+                       static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,
+                       sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags,
+                       k_exp);
+  else if (k_fp8)
+    hipLaunchKernelGGL(store_kernel<2>, dim3((unsigned)blocks), dim3(256), 0, st,
                        static_cast<const uint4*>(src), static_cast<uint4*>(dst),
                        static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,
                        sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags,
                        k_exp);
   else
-    hipLaunchKernelGGL(store_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st,
+    hipLaunchKernelGGL(store_kernel<0>, dim3((unsigned)blocks), dim3(256), 0, st,
                        static_cast<const uint4*>(src), static_cast<uint4*>(dst),
                        static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,
                        sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags, 0);

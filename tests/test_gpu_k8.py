@@ -7,7 +7,7 @@ import torch
 
 import kcache_inputs as ki
 import oracle
-from harness import check_unit, pinned_like, sample_units
+from harness import check_unit, dtype_code, pinned_like, sample_units
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -55,13 +55,14 @@ def check_k8_units(ctx, wl, layer, cache, q, lens, units, N, k_exp=K_EXP, tag=""
     G = wl.H // wl.Hkv
     for (b, h) in units:
         qb, kb, vb = ki.gen_unit(wl, layer, b, h)
-        codes = oracle.e4m3_quantise(kb, oracle.F16, k_exp)
+        code = dtype_code(wl)
+        codes = oracle.e4m3_quantise(kb, code, k_exp)
         # the cache holds exactly these codes
         s = kb.shape[0]
         got = cache.k[b, h // G, :s].cpu().numpy()
         assert np.array_equal(got, codes), "%s stored codes of unit (%d,%d)" % (tag, b, h)
-        r = oracle.decode_unit_k8(qb, codes, k_exp, vb, oracle.F16, N, want_scores=True)
-        r["v"] = oracle.decode16(vb, oracle.F16)
+        r = oracle.decode_unit_k8(qb, codes, k_exp, vb, code, N, want_scores=True)
+        r["v"] = oracle.decode16(vb, code)
         check_unit(r, N, out_h[b, h], idx_h[b, h], w_h[b, h],
                    tag="%s k8 %s layer %d unit (%d,%d)" % (tag, wl.name, layer, b, h))
 
@@ -91,6 +92,26 @@ def test_config1_every_unit(kc, ctx):
     wl = ki.config(1)
     cache, q, lens, _, _ = build_k8_layer(kc, ctx, wl, 0)
     check_k8_units(ctx, wl, 0, cache, q, lens, sample_units(wl, 10 ** 9), wl.N)
+
+
+def test_bf16_store_quantises_every_bit_pattern_exactly(kc, ctx):
+    allbits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    k_new = torch.from_numpy(allbits.view(np.int16)).view(torch.bfloat16).reshape(1, 512, 1, 128)
+    k8 = torch.zeros((1, 1, 512, 128), dtype=torch.uint8, device=DEV)
+    v = torch.zeros((1, 1, 512, 128), dtype=torch.bfloat16, device=DEV)
+    cache = kc.LayerCache(k8, v, k_exp=-4)
+    ctx.prefill_store(cache, k_new.to(DEV), k_new.to(DEV), torch.zeros(1, dtype=torch.int32, device=DEV))
+    ctx.synchronize()
+    torch.cuda.synchronize()
+    want = oracle.e4m3_quantise(allbits, oracle.BF16, -4).reshape(512, 128)
+    assert np.array_equal(k8[0, 0].cpu().numpy(), want)
+
+
+def test_bf16_gqa_layer(kc, ctx):
+    # config 3's per-layer shape (GQA group of 4, bf16) with an 8-bit K cache
+    wl = ki.config(3)
+    cache, q, lens, _, _ = build_k8_layer(kc, ctx, wl, 7, chunk_T=4096)
+    check_k8_units(ctx, wl, 7, cache, q, lens, sample_units(wl, 16, seed=3), wl.N)
 
 
 @pytest.mark.parametrize("cfg,layer,count", [(2, 3, 10), (5, 0, 6)])
@@ -170,7 +191,3 @@ def test_error_paths(kc, ctx):
     with pytest.raises(kc.KCacheError) as e:
         ctx.decode_attention(kc.LayerCache(k8, pinned_like(v), k_exp=99), q, lens_dev, 8)
     assert e.value.status == -1
-    bf = kc.LayerCache(k8, pinned_like(v.to(torch.bfloat16)), k_exp=-5)
-    with pytest.raises(kc.KCacheError) as e:
-        ctx.decode_attention(bf, q.to(torch.bfloat16), lens_dev, 8)
-    assert e.value.status == -2
