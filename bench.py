@@ -452,6 +452,12 @@ def cpu_baseline(wl, L, Lh, n_units, passes, outs, idxs, ws, k_fp8=False):
     wall = time.perf_counter() - t
     units_per_step = L * wl.B * wl.H
     step_s = wall / (n_units * passes) * units_per_step
+    # the same oracle on one thread, on a few of the same units
+    n1 = min(4, n_units)
+    t = time.perf_counter()
+    oracle.decode_attention(q[:n1], K[:n1], V[:n1], code, sl[:n1], wl.N, nthreads=1)
+    wall1 = time.perf_counter() - t
+    step_s1 = wall1 / n1 * units_per_step
     # spot check of the GPU results against the oracle's, same acceptance rule as the tests
     checked = identical = 0
     failures = []
@@ -480,6 +486,7 @@ def cpu_baseline(wl, L, Lh, n_units, passes, outs, idxs, ws, k_fp8=False):
         except AssertionError as e:
             failures.append("%s: %s" % ((l, b, h), e))
     return {"value": wl.B / step_s, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "single_thread_value": wl.B / step_s1,
             "sample": "%d of %d (layer, sequence, head) units of %s, regenerated on the host, "
                       "fp64 oracle with %d threads, %d passes, %.2f s wall (%.1f core-seconds); scaled to "
                       "a full step" % (n_units, units_per_step, wl.name, cores, passes, wall,
