@@ -56,11 +56,14 @@ def parse():
                     help="how a decode step is issued: one captured HIP graph launch (default), "
                          "one kcache_decode_step call, or per-layer store + attention calls")
     ap.add_argument("--lanes", type=int, default=1,
-                    help="streams the layers of a step are dealt over (kcache_decode_step); more "
-                         "than 1 lets consecutive layers overlap, which is only meaningful for "
-                         "the attention in isolation")
+                    help="streams a step is spread over (kcache_decode_step)")
+    ap.add_argument("--split", choices=["sequences", "layers"], default="sequences",
+                    help="what the lanes hold: a share of the batch each, run through all layers "
+                         "in order (keeps every dependency of a real decode step), or whole "
+                         "layers dealt round-robin (only meaningful for the attention in "
+                         "isolation)")
     ap.add_argument("--no-overlap-leg", action="store_true",
-                    help="skip the extra timed pass with two lanes reported under layer_overlap")
+                    help="skip the extra timed passes with two lanes reported under lanes_2")
     ap.add_argument("--hbm-layers", type=int, default=0,
                     help="the first L layers keep their V cache in HBM and run conventional "
                          "attention (the method's second knob, section 3.1 / Table 2); -1 = every "
@@ -153,7 +156,7 @@ def main():
                         idx_out=idxs[l], w_out=ws[l]) for l in range(L)]
     plain = mode == kc.GATHER_ZEROCOPY and not a.unfused   # what the step calls implement
     step_mode = a.step_mode if plain else "calls"
-    ctx.set_step_lanes(a.lanes)
+    ctx.set_step_lanes(a.lanes, split_sequences=(a.split == "sequences"))
     graph = ctx.step_graph(step_layers, wl.H, pos_last, lens_dev, wl.N) \
         if step_mode == "graph" else None
 
@@ -185,27 +188,34 @@ def main():
         step()
     sec_per_step = timed(a.steps)
 
-    # ---- optional: the same step with the layers dealt over two streams
+    # ---- optional: the same step spread over two streams, both ways
     overlap = None
     if plain and not a.no_overlap_leg and a.lanes == 1 and L > 1:
         if graph is not None:
             graph.close()
-        ctx.set_step_lanes(2)
-        g2 = ctx.step_graph(step_layers, wl.H, pos_last, lens_dev, wl.N)
-        ctx.set_step_lanes(1)
+            graph = None
         keep = step
-        step = lambda: g2.launch()
-        for _ in range(a.warmup):
-            step()
-        sec2 = timed(a.steps)
-        g2.close()
+        overlap = {}
+        for what in ("sequences", "layers"):
+            if what == "sequences" and wl.B < 2:
+                continue
+            ctx.set_step_lanes(2, split_sequences=(what == "sequences"))
+            g2 = ctx.step_graph(step_layers, wl.H, pos_last, lens_dev, wl.N)
+            step = lambda: g2.launch()
+            for _ in range(a.warmup):
+                step()
+            sec2 = timed(a.steps)
+            g2.close()
+            overlap[what] = {"ms_per_step": sec2 * 1e3, "tokens_per_s": wl.B / sec2}
+        ctx.set_step_lanes(1)
         step = keep
-        overlap = {"lanes": 2, "ms_per_step": sec2 * 1e3, "tokens_per_s": wl.B / sec2,
-                   "note": "consecutive layers on two streams: the K scan of one layer hides the "
-                           "merge / V-pull tail of the one before.  Valid for the attention in "
-                           "isolation only (every layer's q is given up front); not the headline "
-                           "value"}
-        graph = None
+        overlap["note"] = ("two streams, so that the K scan of one launch hides the merge / V-pull "
+                           "tail of another.  sequences: each stream takes half of the batch "
+                           "through the layers in order, which keeps every dependency of a real "
+                           "decode step; layers: whole layers alternate between the streams, "
+                           "which is only meaningful for the attention in isolation.  Neither is "
+                           "the headline value: their launches overlap, so no per-launch "
+                           "roofline can be quoted for them")
 
     # ---- second pass of the same steps with HIP events around every kernel launch
     # (eager launches: events are not part of a captured graph)
@@ -297,7 +307,7 @@ def main():
                    "gather": a.gather, "path": "fused" if fused_path else "unfused",
                    "k_cache": "e4m3, exponent %d" % K_FP8_EXP if a.k_fp8 else wl.dtype,
                    "pipeline_parts": a.parts, "v_in_hbm_layers": Lh, "step_mode": step_mode,
-                   "lanes": a.lanes,
+                   "lanes": a.lanes, "lane_split": a.split if a.lanes > 1 else None,
                    "k_cache_GiB": L * np.prod(shape) * (1 if a.k_fp8 else 2) / 2 ** 30, "setup_s": round(setup_s, 1)},
         "roofline": roofline,
         "v_gather": {
@@ -318,7 +328,7 @@ def main():
                            "unit": "GB/s", "bytes_per_launch": 2.0 * k_bytes_layer,
                            "avg_launch_ms": full_ms / max(full_n, 1), "launches": full_n},
         "probes": probes,
-        "layer_overlap": overlap,
+        "lanes_2": overlap,
     }
 
     if a.prefill:

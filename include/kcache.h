@@ -116,14 +116,21 @@ typedef enum {
                                 the N kept weights by their sum (section 4 remarks that
                                 TopN "regularized" the softmax; the paper does not say
                                 it renormalises)                                      */
-  KC_OPT_STEP_LANES = 5      /* kcache_decode_step / kcache_step_graph_create: 1 (default)
+  KC_OPT_STEP_LANES = 5,     /* kcache_decode_step / kcache_step_graph_create: 1 (default)
                                 runs the layers one after another on the caller's
-                                stream; 2..4 deals them over that many internal streams
-                                so that the K scan of one layer overlaps the tail (merge
-                                and V pull) of the one before.  Only valid when every
-                                layer's q is available up front, as in a benchmark of
-                                the attention alone: in a model, layer l+1's query
-                                depends on layer l's output                            */
+                                stream; 2..4 spreads the step over that many internal
+                                streams so that the K scan of one launch overlaps the
+                                tail (merge and V pull) of another; see the next option
+                                for what is spread                                     */
+  KC_OPT_STEP_SPLIT = 7      /* what the lanes of a step hold.  0 (default): whole layers,
+                                dealt round-robin - only meaningful when every layer's q
+                                is known up front, as in a benchmark of the attention
+                                alone (in a model, layer l+1's query depends on layer l's
+                                output).  1: the sequences of the batch, a contiguous
+                                share per lane, each share running through the layers in
+                                order on its own stream - sequences are independent
+                                (section 3.3), so this keeps every data dependency of a
+                                real decode step                                       */
 } kc_option;
 
 /* Create a context on `device` (a HIP device ordinal) with a workspace of at

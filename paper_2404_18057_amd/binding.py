@@ -14,7 +14,7 @@ GATHER_ZEROCOPY, GATHER_STAGED = 0, 1
 KERNELS = {"kscan": 0, "select": 1, "gather": 2, "store_k": 3, "store_v": 4, "fused": 5,
            "full": 6}
 OPT_PIPELINE_PARTS, OPT_PROFILE, OPT_STAGED_THREADS, OPT_FUSED, OPT_FUSED_ROWS = 0, 1, 2, 3, 4
-OPT_STEP_LANES, OPT_RENORMALIZE = 5, 6
+OPT_STEP_LANES, OPT_RENORMALIZE, OPT_STEP_SPLIT = 5, 6, 7
 
 _c_i32, _c_i64, _c_p, _c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
 
@@ -277,8 +277,11 @@ class Context:
     def set_renormalize(self, on):
         self.set_option(OPT_RENORMALIZE, 1 if on else 0)
 
-    def set_step_lanes(self, lanes):
+    def set_step_lanes(self, lanes, split_sequences=False):
+        """Streams a step is spread over; split_sequences: each lane takes a share of the
+        batch through all layers (dependency-preserving) instead of whole layers."""
         self.set_option(OPT_STEP_LANES, lanes)
+        self.set_option(OPT_STEP_SPLIT, 1 if split_sequences else 0)
 
     @staticmethod
     def _step_array(layers):

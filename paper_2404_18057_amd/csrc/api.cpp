@@ -112,7 +112,7 @@ struct kc_ctx {
   int* flags = nullptr;  // [0] device-check bits, [16] probe sink
   std::string err;
   int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 1,
-      renorm = 0;
+      renorm = 0, step_split = 0;
   int graphs = 0;          // live step graphs: they hold addresses inside ws / counters
   bool capturing = false;  // a step is being captured into a graph: no profiling events
   hipStream_t lane[kMaxLanes] = {};  // streams of kcache_decode_step with more than one lane
@@ -598,6 +598,11 @@ int kcache_set_option(kc_ctx* c, int32_t option, int64_t value) {
     case KC_OPT_FUSED:
       c->fused = value != 0;
       return KC_OK;
+    case KC_OPT_STEP_SPLIT:
+      if (value != 0 && value != 1)
+        return fail(c, KC_ERR_INVALID_ARG, "step split must be 0 (layers) or 1 (sequences)");
+      c->step_split = (int)value;
+      return KC_OK;
     case KC_OPT_RENORMALIZE:
       c->renorm = value != 0;
       return KC_OK;
@@ -913,11 +918,14 @@ int prepare_step(kc_ctx* c, const char* who, const kc_step_layer* layers, int32_
       return fail(c, KC_ERR_UNSUPPORTED, "%s: layer %d: 8-bit K caches are not supported by "
                   "conventional attention", who, l);
     if ((rc = v_pointer(c, &y.cache, &(*v_maps)[l])) != KC_OK) return rc;
-    need = std::max(need, y.cache.v_in_hbm
-                              ? plan_full(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap).bytes
-                              : plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N,
-                                           y.cache.k_fp8).bytes);
-    kv_max = std::max(kv_max, (size_t)y.cache.B * y.cache.Hkv *
+    // with sequences split over the lanes each launch covers a share of the batch
+    const int nb_max = c->step_split ? (y.cache.B + lanes - 1) / lanes : y.cache.B;
+    for (int nb = std::max(1, nb_max - 1); nb <= nb_max; ++nb)
+      need = std::max(need, y.cache.v_in_hbm
+                                ? plan_full(c, nb, H, y.cache.Hkv, y.cache.S_cap).bytes
+                                : plan_fused(c, nb, H, y.cache.Hkv, y.cache.S_cap, N,
+                                             y.cache.k_fp8).bytes);
+    kv_max = std::max(kv_max, (size_t)nb_max * y.cache.Hkv *
                                   kc::kv_split_for(H / y.cache.Hkv));
   }
   *lane_bytes = round256(need);
@@ -939,31 +947,58 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
     KC_HIP(c, hipEventRecord(c->ev_fork, st));
     for (int i = 0; i < lanes; ++i) KC_HIP(c, hipStreamWaitEvent(c->lane[i], c->ev_fork, 0));
   }
-  for (int l = 0; l < L; ++l) {
-    const kc_step_layer& y = layers[l];
-    const int ln = l % lanes;
+  // one layer (or, with the batch split over the lanes, one share of its sequences)
+  auto enqueue_layer = [&](const kc_step_layer& y, const void* v_map, const int32_t* pos,
+                           const int32_t* lens, int ln) -> int {
     hipStream_t s = lanes > 1 ? c->lane[ln] : st;
     void* ws = static_cast<char*>(c->ws) + lane_bytes * ln;
     int* counters = c->counters + lane_counters * ln;
     if (y.k_new_dev) {
       const kc::Shape sh{y.cache.B, 0, y.cache.Hkv, y.cache.S_cap, 0, y.cache.dtype};
       KernelTimer t(c, KC_KERNEL_STORE_K, s);
-      KC_HIP(c, kc::launch_store(sh, y.k_new_dev, y.cache.k_dev, y.v_new_dev, v_maps[l], pos_dev, 1,
-                                 c->flags, y.cache.v_in_hbm ? 0 : 1, s, y.cache.k_fp8,
-                                 y.cache.k_exp));
+      KC_HIP(c, kc::launch_store(sh, y.k_new_dev, y.cache.k_dev, y.v_new_dev,
+                                 const_cast<void*>(v_map), pos, 1, c->flags,
+                                 y.cache.v_in_hbm ? 0 : 1, s, y.cache.k_fp8, y.cache.k_exp));
     }
-    int rc;
     if (y.cache.v_in_hbm) {
       const FullPlan pl = plan_full(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap);
-      rc = enqueue_full(c, &y.cache, v_maps[l], y.q_dev, H, seq_lens_dev, y.out_dev, pl, ws,
-                        counters, s);
-    } else {
-      const FusedPlan pl =
-          plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N, y.cache.k_fp8);
-      rc = enqueue_fused(c, &y.cache, v_maps[l], y.q_dev, H, seq_lens_dev, N, y.out_dev,
-                         y.idx_out_dev, y.w_out_dev, pl, ws, counters, s);
+      return enqueue_full(c, &y.cache, v_map, y.q_dev, H, lens, y.out_dev, pl, ws, counters, s);
     }
-    if (rc != KC_OK) return rc;
+    const FusedPlan pl =
+        plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N, y.cache.k_fp8);
+    return enqueue_fused(c, &y.cache, v_map, y.q_dev, H, lens, N, y.out_dev, y.idx_out_dev,
+                         y.w_out_dev, pl, ws, counters, s);
+  };
+  for (int l = 0; l < L; ++l) {
+    const kc_step_layer& y = layers[l];
+    if (!c->step_split || lanes == 1) {
+      const int rc = enqueue_layer(y, v_maps[l], pos_dev, seq_lens_dev, l % lanes);
+      if (rc != KC_OK) return rc;
+      continue;
+    }
+    // lane i takes the sequences [b0, b1) of every layer: a view of the layer's tensors
+    const int B = y.cache.B;
+    const size_t kv_rows = (size_t)y.cache.Hkv * y.cache.S_cap;
+    for (int ln = 0; ln < lanes; ++ln) {
+      const int b0 = (int)((int64_t)B * ln / lanes), b1 = (int)((int64_t)B * (ln + 1) / lanes);
+      if (b1 <= b0) continue;
+      kc_step_layer v = y;
+      v.cache.B = b1 - b0;
+      v.cache.k_dev = static_cast<char*>(y.cache.k_dev) +
+                      (size_t)b0 * kv_rows * (y.cache.k_fp8 ? kc::kRowBytes / 2 : kc::kRowBytes);
+      const void* v_map = static_cast<const char*>(v_maps[l]) + (size_t)b0 * kv_rows * kc::kRowBytes;
+      const size_t tok = (size_t)b0 * y.cache.Hkv * kc::kRowBytes;  // new rows [B][1][Hkv][d]
+      if (y.k_new_dev) {
+        v.k_new_dev = static_cast<const char*>(y.k_new_dev) + tok;
+        v.v_new_dev = static_cast<const char*>(y.v_new_dev) + tok;
+      }
+      v.q_dev = static_cast<const char*>(y.q_dev) + (size_t)b0 * H * kc::kRowBytes;
+      v.out_dev = y.out_dev + (size_t)b0 * H * kc::kHeadDim;
+      if (y.idx_out_dev) v.idx_out_dev = y.idx_out_dev + (size_t)b0 * H * N;
+      if (y.w_out_dev) v.w_out_dev = y.w_out_dev + (size_t)b0 * H * N;
+      const int rc = enqueue_layer(v, v_map, pos_dev + b0, seq_lens_dev + b0, ln);
+      if (rc != KC_OK) return rc;
+    }
   }
   if (lanes > 1) {
     for (int i = 0; i < lanes; ++i) {
@@ -972,6 +1007,13 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
     }
   }
   return KC_OK;
+}
+
+// Lanes actually used: no more than there are layers (or, with the batch split, sequences).
+int step_lane_count(const kc_ctx* c, const kc_step_layer* layers, int32_t L) {
+  int most = std::max(L, 1);
+  if (c->step_split && layers && L >= 1) most = std::max(layers[0].cache.B, 1);
+  return std::min(c->step_lanes, most);
 }
 
 int wait_for_earlier_work(kc_ctx* c, hipStream_t st) {
@@ -995,7 +1037,7 @@ int kcache_decode_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_
   if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
   std::vector<void*> v_maps;
   size_t lane_bytes = 0, lane_counters = 0;
-  const int lanes = std::min<int>(c->step_lanes, std::max(L, 1));
+  const int lanes = step_lane_count(c, layers, L);
   int rc = prepare_step(c, "kcache_decode_step", layers, L, H, pos_dev, seq_lens_dev, N, lanes,
                         &v_maps, &lane_bytes, &lane_counters);
   if (rc != KC_OK) return rc;
@@ -1018,7 +1060,7 @@ int kcache_step_graph_create(kc_ctx* c, const kc_step_layer* layers, int32_t L, 
   if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
   std::vector<void*> v_maps;
   size_t lane_bytes = 0, lane_counters = 0;
-  const int lanes = std::min<int>(c->step_lanes, std::max(L, 1));
+  const int lanes = step_lane_count(c, layers, L);
   int rc = prepare_step(c, "kcache_step_graph_create", layers, L, H, pos_dev, seq_lens_dev, N,
                         lanes, &v_maps, &lane_bytes, &lane_counters);
   if (rc != KC_OK) return rc;

@@ -112,6 +112,55 @@ def test_step_equals_per_layer_calls_and_oracle(kc, ctx, lanes):
         check_unit(r, wl.N, out[b, h], idx[b, h], w[b, h], tag="step layer 3 (%d,%d)" % (b, h))
 
 
+@pytest.mark.parametrize("lanes,graph", [(2, False), (3, False), (2, True), (4, True)])
+def test_sequence_split_lanes(kc, ctx, lanes, graph):
+    """Lanes that each take a share of the batch through all layers: launches cover fewer
+    sequences (and may pick another chunk size), so results are compared to the per-layer
+    calls within rounding and to the oracle with the usual rule."""
+    wl = ki.config(1, B=5, S_cap=2600, H=4, Hkv=4)
+    L = 3
+    layers, lens, _ = make_model(kc, ctx, wl, L, hbm_layers=1)
+    lens = lens.clone()
+    lens[2], lens[4] = 700, 1
+    pos = (lens - 1).to(torch.int32)
+    # the wiped newest rows sit at S_cap - 1; with shorter lengths the append goes elsewhere
+    ref = per_layer_reference(ctx, wl, layers, pos, lens)
+    clear(layers)
+    wipe_last(layers, lens)
+    ctx.set_step_lanes(lanes, split_sequences=True)
+    try:
+        if graph:
+            g = ctx.step_graph(layers, wl.H, pos, lens, wl.N)
+            g.launch()
+            ctx.synchronize()
+            g.close()
+        else:
+            ctx.decode_step(layers, wl.H, pos, lens, wl.N)
+            ctx.synchronize()
+    finally:
+        ctx.set_step_lanes(1)
+    torch.cuda.synchronize()
+    ctx.device_check()
+    for y, (o, idx, w) in zip(layers, ref):
+        assert torch.allclose(y["out"], o, rtol=2e-3, atol=1e-3)
+        if idx is not None:
+            assert torch.equal(y["idx_out"], idx)
+            assert torch.allclose(y["w_out"], w, rtol=2e-3, atol=1e-7)
+    lens_h = lens.cpu().numpy()
+    y = layers[2]
+    out, idx, w = y["out"].cpu().numpy(), y["idx_out"].cpu().numpy(), y["w_out"].cpu().numpy()
+    for b in range(wl.B):
+        for h in (0, wl.H - 1):
+            qb, kb, vb = ki.gen_unit(wl, 2, b, h)
+            s = int(lens_h[b])
+            # the cache row at s - 1 was replaced by the appended row (generated row S_cap - 1)
+            kb, vb = kb[:s].copy(), vb[:s].copy()
+            kb[s - 1], vb[s - 1] = ki.gen_unit(wl, 2, b, h)[1][wl.S_cap - 1], \
+                ki.gen_unit(wl, 2, b, h)[2][wl.S_cap - 1]
+            r = oracle_unit(wl, 2, b, h, wl.N, bits=(qb, kb, vb))
+            check_unit(r, wl.N, out[b, h], idx[b, h], w[b, h], tag="split (%d,%d)" % (b, h))
+
+
 @pytest.mark.parametrize("lanes", [1, 2])
 def test_graph_replays_equal_eager_results_with_work_in_between(kc, ctx, lanes):
     wl = ki.config(1, B=2, S_cap=2500)
