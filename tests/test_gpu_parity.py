@@ -396,3 +396,18 @@ def test_seeded_random_shapes(kc, ctx, case):
             K[:, :, b_] = K[:, :, a_]
     res = manual_case(kc, ctx, q, K, V, lens, N, dtype=dtype)
     check_manual(res, lens, N, G=G)
+
+
+def test_context_too_long_for_the_merge_buffer(kc, ctx):
+    """300 000 positions with N = 256: even at the largest chunk size the unit's candidates
+    (37 x 256) exceed the merging workgroup's LDS buffer, so the merge reads them from memory
+    on every pass.  Two heads, one of them with duplicated rows across distant chunks."""
+    rng = np.random.default_rng(31)
+    S, N = 300_000, 256
+    q = rng.standard_normal((1, 2, 128))
+    K = rng.standard_normal((1, 2, S, 128)).astype(np.float32)
+    V = rng.standard_normal((1, 2, S, 128)).astype(np.float32)
+    K[0, 1, 250_000:250_040] = K[0, 1, 10:50]          # exact ties far apart
+    K[0, :, ::997] += 2.5 * q[0][:, None, :] / np.linalg.norm(q[0], axis=-1)[:, None, None] * 11.3
+    res = manual_case(kc, ctx, q, K, V, [S], N)
+    check_manual(res, [S], N)
