@@ -32,6 +32,23 @@ HBM_PEAK_GBPS = 8000.0
 K_FP8_EXP = -5   # cache exponent of the 8-bit K variant: covers |K| < 14 of the synthetic workloads
 
 
+def algorithmic_bytes(wl, lens, k_elem_bytes=2):
+    """Bytes one layer of a decode step has to move, whatever the implementation (Table 1):
+    the K rows of every cached position from HBM (the 2bnhs term of the S~ row) and the N
+    kept V rows of every query head over the host link (the 2bNd term of the A~ row)."""
+    lens = np.asarray(lens, dtype=np.int64)
+    k_bytes = int(lens.sum()) * wl.Hkv * wl.d * k_elem_bytes
+    v_bytes = int(np.minimum(lens, wl.N).sum()) * wl.H * wl.d * 2
+    return k_bytes, v_bytes
+
+
+def eq4_break_even(bw_gpu, bw_h2d, overlapped=False):
+    """s/N above which KCache is no slower than a conventional KV cache (section 3.2,
+    equation (4)): Bandwidth_GPU / Bandwidth_H2D when the V pull follows the K scan; half of
+    it when the two overlap (N rows over the link then only have to beat 2 s rows from HBM)."""
+    return bw_gpu / bw_h2d / (2.0 if overlapped else 1.0)
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -230,9 +247,7 @@ def main():
     ctx.device_check()
 
     units_per_layer = wl.B * wl.H
-    k_bytes_layer = int(lens.astype(np.int64).sum()) * wl.Hkv * wl.d * (1 if a.k_fp8 else 2)
-    n_eff = np.minimum(lens, wl.N).astype(np.int64)
-    v_bytes_layer = int(n_eff.sum()) * wl.H * wl.d * 2
+    k_bytes_layer, v_bytes_layer = algorithmic_bytes(wl, lens, 1 if a.k_fp8 else 2)
     fused_path = prof["fused"][1] > 0 or Lh == L
     scan_ms, scan_n = prof["fused"] if fused_path else prof["kscan"]
     full_ms, full_n = prof["full"]
@@ -426,8 +441,9 @@ def crossover_leg(ctx, kc, wl, cache, q, dev, probes, reps=10):
     hbm, link = probes.get("hbm_stream_read_GBps"), probes.get("zerocopy_row_read_GBps")
     return {"shape": {"B": B, "H": H, "Hkv": wl.Hkv, "dtype": wl.dtype}, "grid": rows,
             "break_even_s_over_N": wins,
-            "eq4_ratio_measured_bandwidths": (hbm / link) if hbm and link else None,
-            "eq4_ratio_with_overlap": (hbm / link / 2) if hbm and link else None}
+            "eq4_ratio_measured_bandwidths": eq4_break_even(hbm, link) if hbm and link else None,
+            "eq4_ratio_with_overlap": (eq4_break_even(hbm, link, overlapped=True)
+                                       if hbm and link else None)}
 
 
 def cpu_baseline(wl, L, Lh, n_units, passes, outs, idxs, ws, k_fp8=False):
