@@ -47,8 +47,9 @@ typedef enum { KC_GATHER_ZEROCOPY = 0, KC_GATHER_STAGED = 1 } kc_gather_mode;
 typedef enum {
   KC_OK = 0,
   KC_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, H % Hkv != 0 ...     */
-  KC_ERR_UNSUPPORTED = -2, /* head_dim other than 128, group size H/Hkv not a power
-                              of two up to 32                                       */
+  KC_ERR_UNSUPPORTED = -2, /* head_dim not 64 / 128 / 256, group size H/Hkv not a
+                              power of two up to 32, or a combination a path does
+                              not serve (see the calls)                             */
   KC_ERR_NOT_PINNED = -3,  /* v_host is not device-mapped host memory (or, with
                               v_in_hbm, not device memory)                           */
   KC_ERR_WORKSPACE = -4,   /* workspace could not be (re)allocated                   */
@@ -59,7 +60,8 @@ typedef enum {
 /* One layer's cache.  Both buffers are owned by the caller.
  * Element (b, hk, t, c) of either cache is at ((b*Hkv + hk)*S_cap + t)*d + c, so
  * the K rows of one (sequence, KV head) form one contiguous stream and every V
- * row is one contiguous 256-byte read (section 3.1: K in HBM, V in CPU memory). */
+ * row is one contiguous read of 2 d bytes, 256 for d = 128 (section 3.1: K in HBM, V in
+ * CPU memory). */
 typedef struct {
   void* k_dev;      /* dev   [B][Hkv][S_cap][d], 16-bit elements                     */
   void* v_host;     /* host  [B][Hkv][S_cap][d], same layout, pinned + mapped; with
@@ -67,19 +69,19 @@ typedef struct {
   int32_t B;        /* sequences                                                     */
   int32_t Hkv;      /* KV heads                                                      */
   int32_t S_cap;    /* capacity in positions                                         */
-  int32_t d;        /* head dimension d_h; must be 128                               */
+  int32_t d;        /* head dimension d_h: 64, 128 or 256 (a row is 2 d bytes)       */
   int32_t dtype;    /* kc_dtype of q, K, V                                           */
   int32_t v_in_hbm; /* 0: V in CPU memory (the method's default placement);
                        1: this layer keeps its V cache in HBM (section 3.1 and the
                        caption of Table 2: the first L layers)                      */
-  int32_t k_fp8;    /* 0: K rows are `dtype` values, 256 bytes each;
+  int32_t k_fp8;    /* 0: K rows are `dtype` values, 2 d bytes each;
                        1: variant with an 8-bit K cache (section 1 names cache
                        quantisation as the other way to cut the bytes a decode step
                        moves): k_dev holds OCP FP8 E4M3 codes, 128 bytes per row,
                        element = value(code) * 2^k_exp.  kcache_prefill_store
                        quantises the 16-bit rows it is given (nearest, ties to even,
-                       saturating at 448).  Served by the fused zero-copy decode
-                       path only                                                   */
+                       saturating at 448).  Needs d = 128; served by the fused
+                       zero-copy decode path only                                  */
   int32_t k_exp;    /* the cache's power-of-two scale exponent, |k_exp| <= 32; used
                        only with k_fp8                                              */
 } kc_layer_cache;
@@ -204,7 +206,9 @@ int kcache_prefill_store(kc_ctx* ctx, const kc_layer_cache* cache, const void* k
  *   stream        hipStream_t; all results are complete in stream order
  * Scores and softmax are fp32; the selection is made on the fp32 scores.
  * A layer with cache->v_in_hbm is accepted too (its N rows then come from HBM);
- * KC_GATHER_STAGED is KC_ERR_UNSUPPORTED for such a layer.
+ * KC_GATHER_STAGED is KC_ERR_UNSUPPORTED for such a layer.  Head dimensions 64 and
+ * 256 and 8-bit K caches are served by the fused zero-copy path only (KC_OPT_FUSED
+ * on, KC_GATHER_ZEROCOPY).
  */
 int kcache_decode_attention(kc_ctx* ctx, const kc_layer_cache* cache, const void* q_dev, int32_t H,
                             const int32_t* seq_lens_dev, int32_t N, float* out_dev,

@@ -349,7 +349,10 @@ int shape_status(const kc_layer_cache* cache, int32_t H, int32_t N, const char**
     return *why = "k_fp8 must be 0 or 1", KC_ERR_INVALID_ARG;
   if (cache->k_fp8 && (cache->k_exp < -32 || cache->k_exp > 32))
     return *why = "k_exp must be in [-32, 32]", KC_ERR_INVALID_ARG;
-  if (cache->d != kc::kHeadDim) return *why = "head dimension must be 128", KC_ERR_UNSUPPORTED;
+  if (cache->d != 64 && cache->d != 128 && cache->d != 256)
+    return *why = "head dimension must be 64, 128 or 256", KC_ERR_UNSUPPORTED;
+  if (cache->k_fp8 && cache->d != kc::kHeadDim)
+    return *why = "an 8-bit K cache needs head dimension 128", KC_ERR_UNSUPPORTED;
   if ((int64_t)cache->B * cache->Hkv * cache->S_cap >= (1ll << 40))
     return *why = "cache too large", KC_ERR_INVALID_ARG;
   if (H == 0) return KC_OK;
@@ -370,18 +373,22 @@ int pick_parts(const kc_ctx* c, int kv_units, size_t k_bytes) {
 }
 
 
+// 1 / sqrt(d_h) for the supported head dimensions (exact constants, not a runtime sqrt).
+float inv_sqrt_d(int d) { return d == 64 ? 0.125f : d == 256 ? 0.0625f : 0.08838834764831845f; }
+
 // Sizes that a fused KCache launch of this shape needs.
 struct FusedPlan {
   int R, chunks_cap, kk;
   size_t bytes;
 };
-FusedPlan plan_fused(const kc_ctx* c, int B, int H, int Hkv, int S_cap, int N, int k_fp8) {
+FusedPlan plan_fused(const kc_ctx* c, int B, int H, int Hkv, int S_cap, int N, int k_fp8,
+                     int d = kc::kHeadDim) {
   const int split = kc::kv_split_for(H / Hkv), G = H / Hkv / split;  // per launch unit
   FusedPlan p;
   p.R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
             ? c->fused_rows
             : kc::fused_rows_per_block(B * Hkv * split, G, S_cap, N,
-                                       k_fp8 ? kc::kRowBytes / 2 : kc::kRowBytes);
+                                       k_fp8 ? d : 2 * d);
   p.chunks_cap = (S_cap + p.R - 1) / p.R;
   p.kk = std::min(N, p.R);
   p.bytes = fused_bytes((size_t)B * H, p.chunks_cap, p.kk, N);
@@ -425,8 +432,9 @@ int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, con
   a.kv_count = B * a.Hkv;
   a.renorm = c->renorm;
   a.k_fp8 = cache->k_fp8;
-  // 1 / sqrt(128), times the cache's 2^k_exp for an 8-bit K cache
-  a.scale = cache->k_fp8 ? ldexpf(0.08838834764831845f, cache->k_exp) : 0.08838834764831845f;
+  a.d = cache->d;
+  // 1 / sqrt(d_h), times the cache's 2^k_exp for an 8-bit K cache
+  a.scale = ldexpf(inv_sqrt_d(cache->d), cache->k_fp8 ? cache->k_exp : 0);
   KernelTimer t(c, KC_KERNEL_FUSED, st);
   KC_HIP(c, kc::launch_fused(a, cache->dtype, a.kv_count, st));
   return KC_OK;
@@ -436,16 +444,16 @@ struct FullPlan {
   int R, chunks_cap;
   size_t part_bytes, bytes;
 };
-FullPlan plan_full(const kc_ctx* c, int B, int H, int Hkv, int S_cap) {
+FullPlan plan_full(const kc_ctx* c, int B, int H, int Hkv, int S_cap, int d = kc::kHeadDim) {
   const int split = kc::kv_split_for(H / Hkv), G = H / Hkv / split;  // per launch unit
   FullPlan p;
   p.R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
             ? c->fused_rows
-            : kc::full_rows_per_block(B * Hkv * split, G, S_cap);
+            : kc::full_rows_per_block(B * Hkv * split, G, S_cap, 2 * d);
   p.chunks_cap = (S_cap + p.R - 1) / p.R;
   const size_t units = (size_t)B * H;
   p.part_bytes = round256(units * p.chunks_cap * sizeof(float2));
-  p.bytes = p.part_bytes + round256(units * p.chunks_cap * kc::kHeadDim * sizeof(float));
+  p.bytes = p.part_bytes + round256(units * p.chunks_cap * d * sizeof(float));
   return p;
 }
 
@@ -469,7 +477,8 @@ int enqueue_full(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, cons
   a.R = pl.R;
   a.chunks_cap = pl.chunks_cap;
   a.kv_count = cache->B * a.Hkv;
-  a.scale = 0.08838834764831845f;  // 1 / sqrt(128)
+  a.d = cache->d;
+  a.scale = inv_sqrt_d(cache->d);
   KernelTimer t(c, KC_KERNEL_FULL, st);
   KC_HIP(c, kc::launch_full(a, cache->dtype, st));
   return KC_OK;
@@ -645,7 +654,7 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
   if ((rc = v_pointer(c, cache, &v_map)) != KC_OK) return rc;
 
   hipStream_t st = (hipStream_t)stream;
-  const kc::Shape sh{cache->B, 0, cache->Hkv, cache->S_cap, 0, cache->dtype};
+  const kc::Shape sh{cache->B, 0, cache->Hkv, cache->S_cap, 0, cache->dtype, 0, cache->d};
   if (cache->v_in_hbm) {
     // both caches in HBM: one launch over the whole grid on the caller's stream
     {
@@ -701,9 +710,10 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
                 gather_mode);
   DeviceGuard g(c->device);
   if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
-  if (cache->k_fp8 && (gather_mode == KC_GATHER_STAGED || !c->fused))
-    return fail(c, KC_ERR_UNSUPPORTED, "kcache_decode_attention: an 8-bit K cache is served by "
-                "the fused zero-copy path only");
+  if ((cache->k_fp8 || cache->d != kc::kHeadDim) &&
+      (gather_mode == KC_GATHER_STAGED || !c->fused))
+    return fail(c, KC_ERR_UNSUPPORTED, "kcache_decode_attention: 8-bit K caches and head "
+                "dimensions other than 128 are served by the fused zero-copy path only");
   if (cache->v_in_hbm && gather_mode == KC_GATHER_STAGED)
     return fail(c, KC_ERR_UNSUPPORTED, "kcache_decode_attention: the staged gather needs the V "
                 "cache in host memory");
@@ -715,7 +725,7 @@ int kcache_decode_attention(kc_ctx* c, const kc_layer_cache* cache, const void* 
   const int kv_units = B * Hkv;
   const bool staged = gather_mode == KC_GATHER_STAGED;
   const bool fused = !staged && c->fused;
-  const FusedPlan pl = plan_fused(c, B, H, Hkv, S_cap, N, cache->k_fp8);
+  const FusedPlan pl = plan_fused(c, B, H, Hkv, S_cap, N, cache->k_fp8, cache->d);
   const size_t need = fused ? pl.bytes : unfused_bytes(units, S_cap, N);
   if ((rc = ensure_workspace(c, need)) != KC_OK) return rc;
   if (staged && (rc = ensure_staged(c, units * N)) != KC_OK) return rc;
@@ -865,7 +875,7 @@ int kcache_full_attention(kc_ctx* c, const kc_layer_cache* cache, const void* q_
   void* v_map = nullptr;
   if ((rc = v_pointer(c, cache, &v_map)) != KC_OK) return rc;
 
-  const FullPlan pl = plan_full(c, cache->B, H, cache->Hkv, cache->S_cap);
+  const FullPlan pl = plan_full(c, cache->B, H, cache->Hkv, cache->S_cap, cache->d);
   if ((rc = ensure_workspace(c, pl.bytes)) != KC_OK) return rc;
   if ((rc = ensure_counters(c, (size_t)cache->B * cache->Hkv *
                                    kc::kv_split_for(H / cache->Hkv))) != KC_OK)
@@ -922,9 +932,9 @@ int prepare_step(kc_ctx* c, const char* who, const kc_step_layer* layers, int32_
     const int nb_max = c->step_split ? (y.cache.B + lanes - 1) / lanes : y.cache.B;
     for (int nb = std::max(1, nb_max - 1); nb <= nb_max; ++nb)
       need = std::max(need, y.cache.v_in_hbm
-                                ? plan_full(c, nb, H, y.cache.Hkv, y.cache.S_cap).bytes
+                                ? plan_full(c, nb, H, y.cache.Hkv, y.cache.S_cap, y.cache.d).bytes
                                 : plan_fused(c, nb, H, y.cache.Hkv, y.cache.S_cap, N,
-                                             y.cache.k_fp8).bytes);
+                                             y.cache.k_fp8, y.cache.d).bytes);
     kv_max = std::max(kv_max, (size_t)nb_max * y.cache.Hkv *
                                   kc::kv_split_for(H / y.cache.Hkv));
   }
@@ -954,18 +964,18 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
     void* ws = static_cast<char*>(c->ws) + lane_bytes * ln;
     int* counters = c->counters + lane_counters * ln;
     if (y.k_new_dev) {
-      const kc::Shape sh{y.cache.B, 0, y.cache.Hkv, y.cache.S_cap, 0, y.cache.dtype};
+      const kc::Shape sh{y.cache.B, 0, y.cache.Hkv, y.cache.S_cap, 0, y.cache.dtype, 0, y.cache.d};
       KernelTimer t(c, KC_KERNEL_STORE_K, s);
       KC_HIP(c, kc::launch_store(sh, y.k_new_dev, y.cache.k_dev, y.v_new_dev,
                                  const_cast<void*>(v_map), pos, 1, c->flags,
                                  y.cache.v_in_hbm ? 0 : 1, s, y.cache.k_fp8, y.cache.k_exp));
     }
     if (y.cache.v_in_hbm) {
-      const FullPlan pl = plan_full(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap);
+      const FullPlan pl = plan_full(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, y.cache.d);
       return enqueue_full(c, &y.cache, v_map, y.q_dev, H, lens, y.out_dev, pl, ws, counters, s);
     }
     const FusedPlan pl =
-        plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N, y.cache.k_fp8);
+        plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N, y.cache.k_fp8, y.cache.d);
     return enqueue_fused(c, &y.cache, v_map, y.q_dev, H, lens, N, y.out_dev, y.idx_out_dev,
                          y.w_out_dev, pl, ws, counters, s);
   };
@@ -979,21 +989,22 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
     // lane i takes the sequences [b0, b1) of every layer: a view of the layer's tensors
     const int B = y.cache.B;
     const size_t kv_rows = (size_t)y.cache.Hkv * y.cache.S_cap;
+    const size_t row_bytes = (size_t)y.cache.d * 2;
     for (int ln = 0; ln < lanes; ++ln) {
       const int b0 = (int)((int64_t)B * ln / lanes), b1 = (int)((int64_t)B * (ln + 1) / lanes);
       if (b1 <= b0) continue;
       kc_step_layer v = y;
       v.cache.B = b1 - b0;
       v.cache.k_dev = static_cast<char*>(y.cache.k_dev) +
-                      (size_t)b0 * kv_rows * (y.cache.k_fp8 ? kc::kRowBytes / 2 : kc::kRowBytes);
-      const void* v_map = static_cast<const char*>(v_maps[l]) + (size_t)b0 * kv_rows * kc::kRowBytes;
-      const size_t tok = (size_t)b0 * y.cache.Hkv * kc::kRowBytes;  // new rows [B][1][Hkv][d]
+                      (size_t)b0 * kv_rows * (y.cache.k_fp8 ? row_bytes / 2 : row_bytes);
+      const void* v_map = static_cast<const char*>(v_maps[l]) + (size_t)b0 * kv_rows * row_bytes;
+      const size_t tok = (size_t)b0 * y.cache.Hkv * row_bytes;  // new rows [B][1][Hkv][d]
       if (y.k_new_dev) {
         v.k_new_dev = static_cast<const char*>(y.k_new_dev) + tok;
         v.v_new_dev = static_cast<const char*>(y.v_new_dev) + tok;
       }
-      v.q_dev = static_cast<const char*>(y.q_dev) + (size_t)b0 * H * kc::kRowBytes;
-      v.out_dev = y.out_dev + (size_t)b0 * H * kc::kHeadDim;
+      v.q_dev = static_cast<const char*>(y.q_dev) + (size_t)b0 * H * row_bytes;
+      v.out_dev = y.out_dev + (size_t)b0 * H * y.cache.d;
       if (y.idx_out_dev) v.idx_out_dev = y.idx_out_dev + (size_t)b0 * H * N;
       if (y.w_out_dev) v.w_out_dev = y.w_out_dev + (size_t)b0 * H * N;
       const int rc = enqueue_layer(v, v_map, pos_dev + b0, seq_lens_dev + b0, ln);

@@ -36,12 +36,27 @@ __device__ __forceinline__ float dpp_add(float x) {
   return x + __builtin_bit_cast(float, y);
 }
 
-// Sum over the 16 lanes of a DPP row, returned to every lane of the row.
-__device__ __forceinline__ float row16_sum(float x) {
+// A cache row of D 16-bit values is LPR = D / 8 lanes x 16 bytes (8, 16 or 32 lanes for
+// D = 64, 128, 256), so one wave-wide 16-byte load reads RPL = 64 / LPR rows.
+template <int D>
+struct RowLayout {
+  static_assert(D == 64 || D == 128 || D == 256, "head dimension must be 64, 128 or 256");
+  static constexpr int LPR = D / 8;
+  static constexpr int RPL = 64 / LPR;
+  // loads a lane keeps in flight per scan iteration, and the rows they cover (at most 64,
+  // so that any chunk size that is a multiple of 64 rows per wave works)
+  static constexpr int LOADS = LPR == 16 ? 16 : 8;  // (32-lane rows: fewer, their sums cost more registers)
+  static constexpr int ROWS = LOADS * RPL;
+};
+
+// Sum over the LPR lanes that hold one row, returned to every one of them.
+template <int LPR>
+__device__ __forceinline__ float row_sum(float x) {
   x = dpp_add<0xB1>(x);   // quad_perm [1,0,3,2]
   x = dpp_add<0x4E>(x);   // quad_perm [2,3,0,1]
-  x = dpp_add<0x141>(x);  // row_half_mirror
-  x = dpp_add<0x140>(x);  // row_mirror
+  x = dpp_add<0x141>(x);  // row_half_mirror: 8 lanes
+  if constexpr (LPR >= 16) x = dpp_add<0x140>(x);  // row_mirror: the 16 lanes of a DPP row
+  if constexpr (LPR == 32) x += __shfl_xor(x, 16, 64);  // the neighbouring DPP row
   return x;
 }
 
@@ -83,54 +98,58 @@ __device__ __forceinline__ T ld_dev(const T* p) {
 // the G query heads of its group, written to z[g * R + local] (LDS); local is the
 // position relative to row0.  Called by all NT threads of the workgroup.
 //
-// A K row is 16 lanes x 16 bytes, so a wave-wide 16-byte load reads 4 rows as one
-// coalesced 1 KiB request; 16 such loads are issued back to back (16 KiB per wave
+// For D = 128 a K row is 16 lanes x 16 bytes, so a wave-wide 16-byte load reads 4 rows
+// as one coalesced 1 KiB request; 16 such loads are issued back to back (16 KiB per wave
 // in flight) with the non-temporal hint.  Each lane multiplies its 8 values with
-// q (fp32 accumulate); the 16 partials of a row are added inside the DPP row.
+// q (fp32 accumulate); the partials of a row are added across its lanes with DPP.
 // Rows at or beyond s are not loaded past S_cap and their scores are not defined.
-template <int DT, int G, int NT>
+template <int DT, int G, int NT, int D = kHeadDim>
 __device__ __forceinline__ void score_chunk(const uint16_t* __restrict__ q_group,
                                             const uint16_t* __restrict__ K_unit, int S_cap, int s,
                                             int row0, int R, float scale, float* z) {
+  typedef RowLayout<D> RL;
+  constexpr int LPR = RL::LPR, RPL = RL::RPL, U = RL::LOADS, ROWS = RL::ROWS;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int sub = lane & 15, rg = lane >> 4;
+  const int sub = lane % LPR, rg = lane / LPR;
   uint4 qv[G];
 #pragma unroll
   for (int g = 0; g < G; ++g)
-    qv[g] = *reinterpret_cast<const uint4*>(q_group + (size_t)g * kHeadDim + sub * 8);
+    qv[g] = *reinterpret_cast<const uint4*>(q_group + (size_t)g * D + sub * 8);
   const uint4* __restrict__ Kp = reinterpret_cast<const uint4*>(K_unit);
   const int rows_per_wave = R / (NT / 64);  // a multiple of 64
 #pragma unroll 1
-  for (int it = 0; it < rows_per_wave / 64; ++it) {
-    const int local = wave * rows_per_wave + it * 64;
+  for (int it = 0; it < rows_per_wave / ROWS; ++it) {
+    const int local = wave * rows_per_wave + it * ROWS;
     const int base = row0 + local;
     if (base >= s) break;
-    uint4 kr[16];
-    if (base + 64 <= S_cap) {
-      const uint4* p = Kp + (size_t)(base + rg) * 16 + sub;
+    uint4 kr[U];
+    if (base + ROWS <= S_cap) {
+      const uint4* p = Kp + (size_t)(base + rg) * LPR + sub;
 #pragma unroll
-      for (int u = 0; u < 16; ++u) kr[u] = load_stream16(p + u * 64);
+      for (int u = 0; u < U; ++u) kr[u] = load_stream16(p + u * 64);
     } else {  // last rows of the cache: never read beyond S_cap
 #pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        int r = base + u * 4 + rg;
+      for (int u = 0; u < U; ++u) {
+        int r = base + u * RPL + rg;
         r = r < S_cap ? r : S_cap - 1;
-        kr[u] = Kp[(size_t)r * 16 + sub];
+        kr[u] = Kp[(size_t)r * LPR + sub];
       }
     }
     float keep[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) keep[g] = 0.f;
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
+    for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float x = row16_sum(dot8<DT>(kr[u], qv[g]));
+        const float x = row_sum<LPR>(dot8<DT>(kr[u], qv[g]));
         keep[g] = (sub == u) ? x : keep[g];
       }
     }
+    if (sub < U) {  // lane `sub` of a row group holds the row of load `sub`
 #pragma unroll
-    for (int g = 0; g < G; ++g) z[g * R + local + sub * 4 + rg] = keep[g] * scale;
+      for (int g = 0; g < G; ++g) z[g * R + local + sub * RPL + rg] = keep[g] * scale;
+    }
   }
 }
 

@@ -44,24 +44,26 @@ constexpr int FW = FT / 64;
 
 constexpr int kStage = 1024;  // entries of each of the two staging arrays inside hist[]
 
+template <int D>
 struct Smem {
   float z[kFusedZFloats];  // scores of this chunk, [G][R]; reused for the merge
   TopNScratch<FT> sc;
-  float red_out[FW * kHeadDim];
+  float red_out[FW * D];
   int last;
 };
 
-// V pull + weighted sum for one unit by the whole workgroup: 32 row slots of 16
-// lanes, 8 independent 256-byte reads per slot in flight.  iu / wu may point to
-// LDS or to global memory.
-template <int DT>
+// V pull + weighted sum for one unit by the whole workgroup: FW * RPL row slots of LPR
+// lanes (32 slots of 16 lanes for D = 128), 8 independent row reads per slot in flight.
+// iu / wu may point to LDS or to global memory.
+template <int DT, int D>
 __device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp, const int32_t* iu,
                                                     const float* wu, int n_eff,
-                                                    float* __restrict__ out_u, Smem* sm) {
+                                                    float* __restrict__ out_u, Smem<D>* sm) {
+  constexpr int LPR = RowLayout<D>::LPR, RPL = RowLayout<D>::RPL;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int sub = lane & 15, rg = lane >> 4;
-  const int slot = wave * 4 + rg;
-  constexpr int SLOTS = FW * 4, UNR = 8;
+  const int sub = lane % LPR, rg = lane / LPR;
+  const int slot = wave * RPL + rg;
+  constexpr int SLOTS = FW * RPL, UNR = 8;
   float acc[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) acc[i] = 0.f;
@@ -78,26 +80,27 @@ __device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
       v[u] = make_uint4(0, 0, 0, 0);
-      if (t[u] >= 0) v[u] = Vp[(size_t)t[u] * 16 + sub];
+      if (t[u] >= 0) v[u] = Vp[(size_t)t[u] * LPR + sub];
     }
 #pragma unroll
     for (int u = 0; u < UNR; ++u)
       if (t[u] >= 0) fma8<DT>(acc, v[u], w[u]);
   }
+  // add the row groups of the wave (lanes that hold the same channels), then the waves
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    acc[i] += __shfl_xor(acc[i], 16, 64);
-    acc[i] += __shfl_xor(acc[i], 32, 64);
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) acc[i] += __shfl_xor(acc[i], m, 64);
   }
   if (rg == 0) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) sm->red_out[wave * kHeadDim + sub * 8 + i] = acc[i];
+    for (int i = 0; i < 8; ++i) sm->red_out[wave * D + sub * 8 + i] = acc[i];
   }
   __syncthreads();
-  if (threadIdx.x < kHeadDim) {
+  if (threadIdx.x < D) {
     float t = 0.f;
 #pragma unroll
-    for (int w = 0; w < FW; ++w) t += sm->red_out[w * kHeadDim + threadIdx.x];
+    for (int w = 0; w < FW; ++w) t += sm->red_out[w * D + threadIdx.x];
     out_u[threadIdx.x] = t;
   }
   __syncthreads();
@@ -107,10 +110,10 @@ __device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp
 // would allow: measured on MI355X the launch is 3-7 % faster that way on the
 // large workloads (fewer units in flight per XCD, so units complete and start
 // pulling V earlier, and less contention for the CU while a workgroup selects).
-template <int DT, int G, bool K8>
+template <int DT, int G, bool K8, int D>
 __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void fused_kernel(
     FusedArgs a) {
-  __shared__ Smem sm;
+  __shared__ Smem<D> sm;
   const int tid = threadIdx.x;
   // XCD-aware mapping.  Workgroups are handed to the 8 XCDs round-robin in launch
   // order, so block b runs on XCD b % 8.  All chunks of a KV unit are given to one
@@ -140,7 +143,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
           a.idx[(size_t)(unit0 + g) * N + j] = -1;
           a.w[(size_t)(unit0 + g) * N + j] = 0.f;
         }
-        if (tid < kHeadDim) a.out[(size_t)(unit0 + g) * kHeadDim + tid] = 0.f;
+        if (tid < D) a.out[(size_t)(unit0 + g) * D + tid] = 0.f;
       }
     }
     return;
@@ -153,12 +156,12 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 
   // ---------------- 1. scores of R positions for the G heads of the group -> LDS
   if constexpr (K8)  // K rows are E4M3 codes, 128 bytes each
-    score_chunk8<DT, G, FT>(a.q + (size_t)unit0 * kHeadDim,
-                        reinterpret_cast<const uint8_t*>(a.K) + kv_phys * a.S_cap * kHeadDim,
-                        a.S_cap, s, row0, R, a.scale, sm.z);
+    score_chunk8<DT, G, FT>(a.q + (size_t)unit0 * D,
+                            reinterpret_cast<const uint8_t*>(a.K) + kv_phys * a.S_cap * D,
+                            a.S_cap, s, row0, R, a.scale, sm.z);
   else
-    score_chunk<DT, G, FT>(a.q + (size_t)unit0 * kHeadDim, a.K + kv_phys * a.S_cap * kHeadDim,
-                           a.S_cap, s, row0, R, a.scale, sm.z);
+    score_chunk<DT, G, FT, D>(a.q + (size_t)unit0 * D, a.K + kv_phys * a.S_cap * D, a.S_cap, s,
+                              row0, R, a.scale, sm.z);
   __syncthreads();
   KC_T(t1);
   KC_TADD(0, t1 - t0);
@@ -230,7 +233,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const bool z_in_lds = M <= kFusedZFloats, pos_in_lds = 2 * M <= kFusedZFloats;
   const bool stage_out = n_eff <= kStage;
   const uint4* __restrict__ Vp =
-      reinterpret_cast<const uint4*>(a.V) + kv_phys * a.S_cap * 16;
+      reinterpret_cast<const uint4*>(a.V) + kv_phys * a.S_cap * (D / 8);
 #pragma unroll 1
   for (int g = 0; g < G; ++g) {
     const int unit = unit0 + g;
@@ -339,28 +342,39 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     // block_topn ended with a barrier: positions and weights are visible to everyone
     KC_T(f2);
     KC_TADD(5, f2 - f1);
-    pull_and_accumulate<DT>(Vp, stage_out ? stage_i : iu, stage_out ? stage_f : wu, n_eff,
-                            a.out + (size_t)unit * kHeadDim, &sm);
+    pull_and_accumulate<DT, D>(Vp, stage_out ? stage_i : iu, stage_out ? stage_f : wu, n_eff,
+                               a.out + (size_t)unit * D, &sm);
     KC_T(f3);
     KC_TADD(6, f3 - f2);
     KC_TADD(8, 1);
   }
 }
 
-template <int DT, bool K8>
+template <int DT, bool K8, int D>
 hipError_t launch_dt(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
   // eight XCDs each get ceil(kv_count / 8) units' worth of blocks
   const long long per_xcd = (long long)((kv_count + kXcds - 1) / kXcds) * a.chunks_cap;
   if (per_xcd * kXcds > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(per_xcd * kXcds)), block(FT);
   switch (G) {
-    case 1: hipLaunchKernelGGL((fused_kernel<DT, 1, K8>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((fused_kernel<DT, 2, K8>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((fused_kernel<DT, 4, K8>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((fused_kernel<DT, 8, K8>), grid, block, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((fused_kernel<DT, 1, K8, D>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((fused_kernel<DT, 2, K8, D>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((fused_kernel<DT, 4, K8, D>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((fused_kernel<DT, 8, K8, D>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_d(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
+  if (a.k_fp8) return a.d == 128 ? launch_dt<DT, true, 128>(a, G, kv_count, st) : hipErrorInvalidValue;
+  switch (a.d) {
+    case 64: return launch_dt<DT, false, 64>(a, G, kv_count, st);
+    case 128: return launch_dt<DT, false, 128>(a, G, kv_count, st);
+    case 256: return launch_dt<DT, false, 256>(a, G, kv_count, st);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace
@@ -375,7 +389,7 @@ hipError_t launch_dt(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N, int k_row_bytes) {
   const int cap = kFusedZFloats / G;
   // the same K bytes per workgroup whatever the row size: an 8-bit K cache takes 2048 rows
-  int R = 1024 * (kRowBytes / k_row_bytes);
+  int R = 1024 * kRowBytes / k_row_bytes;  // 512 rows of 512 bytes ... 2048 rows of 128 bytes
   while (R < cap && (int64_t)((S_cap + R - 1) / R) * (N < R ? N : R) > kFusedZFloats) R *= 2;
   if (R > cap) R = cap;
   // small problems: more, smaller workgroups as long as the merge still fits
@@ -389,11 +403,7 @@ hipError_t launch_fused(const FusedArgs& a, int dtype, int kv_count, hipStream_t
   if (kv_count <= 0) return hipSuccess;
   const int G = a.H / a.Hkv;
   if (a.R % kFusedThreads != 0 || a.R * G > kFusedZFloats) return hipErrorInvalidValue;
-  if (a.k_fp8)
-    return dtype == 0 ? launch_dt<0, true>(a, G, kv_count, st)
-                      : launch_dt<1, true>(a, G, kv_count, st);
-  return dtype == 0 ? launch_dt<0, false>(a, G, kv_count, st)
-                    : launch_dt<1, false>(a, G, kv_count, st);
+  return dtype == 0 ? launch_d<0>(a, G, kv_count, st) : launch_d<1>(a, G, kv_count, st);
 }
 
 }  // namespace kc

@@ -24,19 +24,22 @@ namespace {
 constexpr int AT = kFusedThreads;
 constexpr int AW = AT / 64;
 
+template <int D>
 struct FullSmem {
   float z[kFusedZFloats];  // scores, then softmax numerators, [G][R]; reused by the merge
   TopNScratch<AT> sc;      // reduction scratch
-  float red[AW * kHeadDim];
+  float red[AW * D];
   int last;
 };
 
-template <int DT, int G>
+template <int DT, int G, int D>
 __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void full_kernel(
     FullArgs a) {
-  __shared__ FullSmem sm;
+  typedef RowLayout<D> RL;
+  constexpr int LPR = RL::LPR, RPL = RL::RPL;
+  __shared__ FullSmem<D> sm;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int sub = lane & 15, rg = lane >> 4;
+  const int sub = lane % LPR, rg = lane / LPR;
   // all chunks of a KV unit run on one XCD, unit u on XCD u % 8 (workgroups are
   // dealt to the XCDs round-robin in launch order)
   const int xcd = blockIdx.x % kXcds, in_xcd = blockIdx.x / kXcds;
@@ -53,8 +56,8 @@ __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   }
   const int unit0 = b * a.H + hk * G;
   if (s == 0) {
-    if (chunk == 0 && tid < kHeadDim)
-      for (int g = 0; g < G; ++g) a.out[(size_t)(unit0 + g) * kHeadDim + tid] = 0.f;
+    if (chunk == 0 && tid < D)
+      for (int g = 0; g < G; ++g) a.out[(size_t)(unit0 + g) * D + tid] = 0.f;
     return;
   }
   const int row0 = chunk * R;
@@ -63,8 +66,8 @@ __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const int n = (s - row0 < R) ? s - row0 : R;
 
   // ---------------- 1. scores -> LDS
-  score_chunk<DT, G, AT>(a.q + (size_t)unit0 * kHeadDim, a.K + kv_phys * a.S_cap * kHeadDim,
-                         a.S_cap, s, row0, R, a.scale, sm.z);
+  score_chunk<DT, G, AT, D>(a.q + (size_t)unit0 * D, a.K + kv_phys * a.S_cap * D, a.S_cap, s,
+                            row0, R, a.scale, sm.z);
   __syncthreads();
 
   // ---------------- 2. per head: chunk maximum, numerators in place, their sum
@@ -105,56 +108,57 @@ __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[g][i] = 0.f;
   {
-    const uint4* __restrict__ Vp =
-        reinterpret_cast<const uint4*>(a.V + kv_phys * a.S_cap * kHeadDim);
+    const uint4* __restrict__ Vp = reinterpret_cast<const uint4*>(a.V + kv_phys * a.S_cap * D);
+    constexpr int ROWS = RL::ROWS, U = RL::LOADS;
     const int rows_per_wave = R / AW;
 #pragma unroll 1
-    for (int it = 0; it < rows_per_wave / 64; ++it) {
-      const int local = wave * rows_per_wave + it * 64;
+    for (int it = 0; it < rows_per_wave / ROWS; ++it) {
+      const int local = wave * rows_per_wave + it * ROWS;
       const int base = row0 + local;
       if (base >= s) break;
-      constexpr int VB = (G >= 4) ? 8 : 16;  // rows per lane in flight; fewer when G accumulators need the registers
+      // rows per lane in flight; fewer when G accumulators need the registers
+      constexpr int VB = (G >= 4 && U > 8) ? 8 : U;
 #pragma unroll 1
-      for (int h = 0; h < 16; h += VB) {
+      for (int h = 0; h < U; h += VB) {
         uint4 vr[VB];
-        if (base + 64 <= s) {
-          const uint4* p = Vp + (size_t)(base + rg) * 16 + sub;
+        if (base + ROWS <= s) {
+          const uint4* p = Vp + (size_t)(base + rg) * LPR + sub;
 #pragma unroll
           for (int u = 0; u < VB; ++u) vr[u] = load_stream16(p + (h + u) * 64);
         } else {  // ragged end: rows at or beyond the length are neither read nor used
 #pragma unroll
           for (int u = 0; u < VB; ++u) {
-            const int r = base + (h + u) * 4 + rg;
-            vr[u] = (r < s) ? Vp[(size_t)r * 16 + sub] : make_uint4(0, 0, 0, 0);
+            const int r = base + (h + u) * RPL + rg;
+            vr[u] = (r < s) ? Vp[(size_t)r * LPR + sub] : make_uint4(0, 0, 0, 0);
           }
         }
 #pragma unroll
         for (int u = 0; u < VB; ++u) {
 #pragma unroll
           for (int g = 0; g < G; ++g)
-            fma8<DT>(acc[g], vr[u], sm.z[g * R + local + (h + u) * 4 + rg]);
+            fma8<DT>(acc[g], vr[u], sm.z[g * R + local + (h + u) * RPL + rg]);
         }
       }
     }
   }
-  // add the 4 row groups of a wave, then the waves; one head at a time through LDS
+  // add the row groups of a wave, then the waves; one head at a time through LDS
 #pragma unroll
   for (int g = 0; g < G; ++g) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      acc[g][i] += __shfl_xor(acc[g][i], 16, 64);
-      acc[g][i] += __shfl_xor(acc[g][i], 32, 64);
+#pragma unroll
+      for (int m = LPR; m < 64; m <<= 1) acc[g][i] += __shfl_xor(acc[g][i], m, 64);
     }
     if (rg == 0) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) sm.red[wave * kHeadDim + sub * 8 + i] = acc[g][i];
+      for (int i = 0; i < 8; ++i) sm.red[wave * D + sub * 8 + i] = acc[g][i];
     }
     __syncthreads();
-    if (tid < kHeadDim) {
+    if (tid < D) {
       float t = 0.f;
 #pragma unroll
-      for (int w = 0; w < AW; ++w) t += sm.red[w * kHeadDim + tid];
-      st_dev(a.part_o + ((size_t)(unit0 + g) * a.chunks_cap + chunk) * kHeadDim + tid, t);
+      for (int w = 0; w < AW; ++w) t += sm.red[w * D + tid];
+      st_dev(a.part_o + ((size_t)(unit0 + g) * a.chunks_cap + chunk) * D + tid, t);
     }
     __syncthreads();
   }
@@ -176,8 +180,8 @@ __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   if (!sm.last) return;
 
   float* fac = sm.z;  // e^(m_c - M) per chunk, at most kFusedZFloats chunks at a time
-  const int c_lane = tid & (kHeadDim - 1), c_grp = tid >> 7;  // 4 groups of 128 channels
-  constexpr int GRPS = AT / kHeadDim;
+  const int c_lane = tid % D, c_grp = tid / D;  // AT / D groups of D channels
+  constexpr int GRPS = AT / D;
 #pragma unroll 1
   for (int g = 0; g < G; ++g) {
     const size_t slot0 = (size_t)(unit0 + g) * a.chunks_cap;
@@ -201,7 +205,7 @@ __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           const int cc = c + u * GRPS;
-          v[u] = (cc < cn) ? ld_dev(a.part_o + (slot0 + c0 + cc) * kHeadDim + c_lane) : 0.f;
+          v[u] = (cc < cn) ? ld_dev(a.part_o + (slot0 + c0 + cc) * D + c_lane) : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -210,31 +214,41 @@ __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
         }
       }
     }
-    sm.red[c_grp * kHeadDim + c_lane] = o;
+    sm.red[c_grp * D + c_lane] = o;
     __syncthreads();
-    if (tid < kHeadDim) {
+    if (tid < D) {
       float t = 0.f;
 #pragma unroll
-      for (int w = 0; w < GRPS; ++w) t += sm.red[w * kHeadDim + tid];
-      a.out[(size_t)(unit0 + g) * kHeadDim + tid] = t / ML.y;
+      for (int w = 0; w < GRPS; ++w) t += sm.red[w * D + tid];
+      a.out[(size_t)(unit0 + g) * D + tid] = t / ML.y;
     }
     __syncthreads();
   }
 }
 
-template <int DT>
+template <int DT, int D>
 hipError_t launch_dt(const FullArgs& a, int G, hipStream_t st) {
   const long long per_xcd = (long long)((a.kv_count + kXcds - 1) / kXcds) * a.chunks_cap;
   if (per_xcd * kXcds > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(per_xcd * kXcds)), block(AT);
   switch (G) {
-    case 1: hipLaunchKernelGGL((full_kernel<DT, 1>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((full_kernel<DT, 2>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((full_kernel<DT, 4>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((full_kernel<DT, 8>), grid, block, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((full_kernel<DT, 1, D>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((full_kernel<DT, 2, D>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((full_kernel<DT, 4, D>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((full_kernel<DT, 8, D>), grid, block, 0, st, a); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+template <int DT>
+hipError_t launch_d(const FullArgs& a, int G, hipStream_t st) {
+  switch (a.d) {
+    case 64: return launch_dt<DT, 64>(a, G, st);
+    case 128: return launch_dt<DT, 128>(a, G, st);
+    case 256: return launch_dt<DT, 256>(a, G, st);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace
@@ -242,8 +256,8 @@ hipError_t launch_dt(const FullArgs& a, int G, hipStream_t st) {
 // Positions per workgroup: 1024 (as in the fused KCache kernel), less when the
 // group's scores would not fit the LDS buffer or the launch would be too small
 // to fill the chip.
-int full_rows_per_block(int kv_units, int G, int S_cap) {
-  int R = 1024;
+int full_rows_per_block(int kv_units, int G, int S_cap, int row_bytes) {
+  int R = 1024 * kRowBytes / row_bytes;  // the same bytes per workgroup whatever the row size
   if (R * G > kFusedZFloats) R = kFusedZFloats / G;
   while (R > kFusedThreads && (int64_t)kv_units * ((S_cap + R - 1) / R) < 512) R /= 2;
   return R;
@@ -253,7 +267,7 @@ hipError_t launch_full(const FullArgs& a, int dtype, hipStream_t st) {
   if (a.kv_count <= 0) return hipSuccess;
   const int G = a.H / a.Hkv;
   if (a.R % kFusedThreads != 0 || a.R * G > kFusedZFloats) return hipErrorInvalidValue;
-  return dtype == 0 ? launch_dt<0>(a, G, st) : launch_dt<1>(a, G, st);
+  return dtype == 0 ? launch_d<0>(a, G, st) : launch_d<1>(a, G, st);
 }
 
 }  // namespace kc

@@ -34,6 +34,7 @@ inline int kv_split_for(int G) { return G > 8 ? G / 8 : 1; }
 struct Shape {
   int B, H, Hkv, S_cap, N, dtype;
   int renorm = 0;  // 1: kept weights are divided by their sum
+  int d = kHeadDim;  // head dimension (the store handles 64, 128, 256; the unfused kernels 128)
 };
 
 // Scores z[b][h][t] = (q[b][h] . K[b][h/G][t]) / sqrt(d_h) for the KV units
@@ -86,6 +87,7 @@ struct FusedArgs {
   int renorm;      // 1: kept weights are divided by their sum
   int kv_split;    // launch units per physical KV head (see kv_split_for)
   int k_fp8;       // 1: K rows are E4M3 codes (128 bytes per row); scale carries 2^k_exp
+  int d;           // head dimension: 64, 128 or 256
   float scale;
 };
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N, int k_row_bytes);
@@ -107,9 +109,10 @@ struct FullArgs {
   int chunks_cap;  // ceil(S_cap / R)
   int kv_count;
   int kv_split;    // launch units per physical KV head (see kv_split_for)
+  int d;           // head dimension: 64, 128 or 256
   float scale;
 };
-int full_rows_per_block(int kv_units, int G, int S_cap);
+int full_rows_per_block(int kv_units, int G, int S_cap, int row_bytes);
 hipError_t launch_full(const FullArgs& a, int dtype, hipStream_t st);
 
 hipError_t launch_probe_read(const void* ptr, size_t bytes, uint32_t* sink, hipStream_t st);

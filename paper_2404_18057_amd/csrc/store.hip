@@ -21,12 +21,12 @@ namespace {
 
 constexpr int kHostStoreBlocks = 20;  // workgroups of a store whose destination is host memory
 constexpr int kTokTile = 4;    // tokens per workgroup
-constexpr int kHeadTile = 16;  // KV heads per workgroup, four per pass
 
-// A workgroup moves a tile of 4 tokens x 16 KV heads.  In each of its four passes
-// the 16 row groups cover 4 tokens x 4 heads: the 4 heads of a token are 1 KiB of
-// contiguous source, the 4 tokens of a head are 1 KiB of contiguous destination.
-// All index arithmetic is 32-bit and done once per workgroup.
+// A row of D 16-bit values is LPR = D / 8 lanes x 16 bytes, so the 256 threads form
+// 256 / LPR row groups.  A workgroup moves a tile of 4 tokens x HEADS KV heads in four
+// passes; in each pass the row groups cover 4 tokens x (row groups / 4) heads.  For
+// D = 128: 16 row groups, 4 tokens x 4 heads per pass - the 4 heads of a token are 1 KiB
+// of contiguous source, the 4 tokens of a head are 1 KiB of contiguous destination.
 //
 // src2 / dst2, when not null, are a second tensor pair moved with the same
 // indices (the K and V rows of a decode-step append in one launch).
@@ -77,8 +77,8 @@ __device__ __forceinline__ uint2 quant_row8(const uint4& v, int k_exp) {
                     c[4] | (c[5] << 8) | (c[6] << 16) | (c[7] << 24));
 }
 
-// K8: 0 = plain copy, 1 = quantise fp16 rows, 2 = quantise bf16 rows
-template <int K8>
+// K8: 0 = plain copy, 1 = quantise fp16 rows, 2 = quantise bf16 rows (LPR 16 only)
+template <int K8, int LPR>
 __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ src,
                                                     uint4* __restrict__ dst,
                                                     const uint4* __restrict__ src2,
@@ -87,8 +87,10 @@ __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ sr
                                                     int Hkv, int S_cap, int t_tiles, int h_tiles,
                                                     unsigned total_tiles,
                                                     int* __restrict__ flags, int k_exp) {
-  const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
-  const int ti = grp >> 2, hi = grp & 3;
+  constexpr int HPP = 256 / LPR / kTokTile;  // heads per pass
+  constexpr int kHeadTile = 4 * HPP;         // heads per workgroup
+  const int sub = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  const int ti = grp / HPP, hi = grp % HPP;
   for (unsigned tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
     const unsigned ht = tile % (unsigned)h_tiles;
     const unsigned rest = tile / (unsigned)h_tiles;
@@ -102,16 +104,16 @@ __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ sr
     bool ok[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int hk = (int)ht * kHeadTile + i * 4 + hi;
+      const int hk = (int)ht * kHeadTile + i * HPP + hi;
       ok[i] = t_ok && p_ok && hk < Hkv;
-      const size_t from = (((size_t)b * T + t) * Hkv + hk) * 16 + sub;
+      const size_t from = (((size_t)b * T + t) * Hkv + hk) * LPR + sub;
       if (ok[i]) v[i] = src[from];
       if (ok[i] && src2) v2[i] = src2[from];
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int hk = (int)ht * kHeadTile + i * 4 + hi;
-      const size_t to = (((size_t)b * Hkv + hk) * S_cap + (size_t)p) * 16 + sub;
+      const int hk = (int)ht * kHeadTile + i * HPP + hi;
+      const size_t to = (((size_t)b * Hkv + hk) * S_cap + (size_t)p) * LPR + sub;
       if (ok[i]) {
         if constexpr (K8 != 0)
           reinterpret_cast<uint2*>(dst)[to] = quant_row8<K8 - 1>(v[i], k_exp);
@@ -129,30 +131,33 @@ hipError_t launch_store(const Shape& sh, const void* src, void* dst, const void*
                         const int32_t* pos, int T, int* flags, int dst_is_host, hipStream_t st,
                         int k_fp8, int k_exp) {
   if (sh.B <= 0 || T <= 0 || sh.Hkv <= 0) return hipSuccess;
+  if (sh.d != 64 && sh.d != 128 && sh.d != 256) return hipErrorInvalidValue;
+  if (k_fp8 && sh.d != 128) return hipErrorInvalidValue;
+  const int lpr = sh.d / 8;
+  const long long head_tile = 4 * (256 / lpr / kTokTile);
   const long long t_tiles = (T + kTokTile - 1) / kTokTile;
-  const long long h_tiles = (sh.Hkv + kHeadTile - 1) / kHeadTile;
+  const long long h_tiles = (sh.Hkv + head_tile - 1) / head_tile;
   const long long tiles = (long long)sh.B * t_tiles * h_tiles;
   if (tiles > 0xffffffffLL) return hipErrorInvalidValue;
   long long blocks = tiles;
   const long long cap = dst_is_host ? kHostStoreBlocks : 0x7fffffffLL;
   if (blocks > cap) blocks = cap;
+#define KC_STORE(K8, LPR)                                                                       \
+  hipLaunchKernelGGL((store_kernel<K8, LPR>), dim3((unsigned)blocks), dim3(256), 0, st,         \
+                     static_cast<const uint4*>(src), static_cast<uint4*>(dst),                  \
+                     static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,  \
+                     sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags, k_exp)
   if (k_fp8 && sh.dtype == 0)
-    hipLaunchKernelGGL(store_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, st,
-                       static_cast<const uint4*>(src), static_cast<uint4*>(dst),
-                       static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,
-                       sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags,
-                       k_exp);
+    KC_STORE(1, 16);
   else if (k_fp8)
-    hipLaunchKernelGGL(store_kernel<2>, dim3((unsigned)blocks), dim3(256), 0, st,
-                       static_cast<const uint4*>(src), static_cast<uint4*>(dst),
-                       static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,
-                       sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags,
-                       k_exp);
+    KC_STORE(2, 16);
+  else if (lpr == 8)
+    KC_STORE(0, 8);
+  else if (lpr == 16)
+    KC_STORE(0, 16);
   else
-    hipLaunchKernelGGL(store_kernel<0>, dim3((unsigned)blocks), dim3(256), 0, st,
-                       static_cast<const uint4*>(src), static_cast<uint4*>(dst),
-                       static_cast<const uint4*>(src2), static_cast<uint4*>(dst2), pos, sh.B, T,
-                       sh.Hkv, sh.S_cap, (int)t_tiles, (int)h_tiles, (unsigned)tiles, flags, 0);
+    KC_STORE(0, 32);
+#undef KC_STORE
   return hipGetLastError();
 }
 

@@ -34,7 +34,9 @@ def test_workspace_size_formula():
 @pytest.mark.parametrize("args,status", [
     ((1, 8, 2048, 128, 0, 8, 64), 0),
     ((16, 8, 8192, 128, 1, 32, 128), 0),      # GQA group of 4, bf16
-    ((1, 8, 2048, 64, 0, 8, 64), -2),         # head_dim other than 128
+    ((1, 8, 2048, 64, 0, 8, 64), 0),          # head_dim 64
+    ((1, 8, 2048, 256, 1, 8, 64), 0),         # head_dim 256
+    ((1, 8, 2048, 96, 0, 8, 64), -2),         # head_dim other than 64 / 128 / 256
     ((1, 8, 2048, 128, 0, 24, 64), -2),       # group of 3
     ((1, 2, 2048, 128, 0, 32, 64), 0),        # 32 query heads over 2 KV groups: group of 16
     ((1, 1, 2048, 128, 0, 64, 64), -2),       # group of 64
