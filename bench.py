@@ -85,6 +85,11 @@ def parse():
                     help="the first L layers keep their V cache in HBM and run conventional "
                          "attention (the method's second knob, section 3.1 / Table 2); -1 = every "
                          "layer, i.e. the conventional KV-cache baseline")
+    ap.add_argument("--gqa-dedup", action="store_true",
+                    help="grouped queries: pull the union of a group's V rows once")
+    ap.add_argument("--shared-pivots", action="store_true",
+                    help="synthetic variant of the workload in which the heads of a group share "
+                         "their pivotal positions (what --gqa-dedup is for)")
     ap.add_argument("--k-fp8", action="store_true",
                     help="variant: 8-bit K cache (E4M3 codes, cache exponent -5); halves the bytes "
                          "of the K scan")
@@ -109,6 +114,8 @@ def main():
     import paper_2404_18057_amd as kc
 
     wl = ki.config(a.config)
+    if a.shared_pivots:
+        wl = wl.replace(shared_pivots=True, name=wl.name + "_shared_pivots")
     L = a.layers if a.layers > 0 else wl.L
     Lh = L if a.hbm_layers < 0 else min(a.hbm_layers, L)   # layers with V in HBM
     dev = torch.device("cuda:0")
@@ -117,6 +124,7 @@ def main():
     ctx.set_pipeline_parts(a.parts)
     ctx.set_fused(not a.unfused)
     ctx.set_fused_rows(a.rows)
+    ctx.set_gqa_dedup(a.gqa_dedup)
     mode = kc.GATHER_ZEROCOPY if a.gather == "zerocopy" else kc.GATHER_STAGED
     dt = ki.torch_dtype(wl.dtype)
     lens = wl.seq_lens()
@@ -321,6 +329,7 @@ def main():
                    "kv_heads": wl.Hkv, "head_dim": wl.d, "context": int(lens.max()), "top_n": wl.N,
                    "gather": a.gather, "path": "fused" if fused_path else "unfused",
                    "k_cache": "e4m3, exponent %d" % K_FP8_EXP if a.k_fp8 else wl.dtype,
+                   "gqa_dedup": a.gqa_dedup,
                    "pipeline_parts": a.parts, "v_in_hbm_layers": Lh, "step_mode": step_mode,
                    "lanes": a.lanes, "lane_split": a.split if a.lanes > 1 else None,
                    "k_cache_GiB": L * np.prod(shape) * (1 if a.k_fp8 else 2) / 2 ** 30, "setup_s": round(setup_s, 1)},

@@ -124,6 +124,13 @@ typedef enum {
                                 streams so that the K scan of one launch overlaps the
                                 tail (merge and V pull) of another; see the next option
                                 for what is spread                                     */
+  KC_OPT_GQA_DEDUP = 8,      /* 1: with grouped queries the fused launch pulls the union of
+                                the rows that the heads of a group selected, each row
+                                once, instead of every head's rows separately (same
+                                results up to summation order; pays when the heads of a
+                                group attend to the same positions).  Used when
+                                (H/Hkv)^2 * N <= 2048 and s <= 131072, otherwise the
+                                per-head pull runs.  0 (default): per-head pulls       */
   KC_OPT_STEP_SPLIT = 7      /* what the lanes of a step hold.  0 (default): whole layers,
                                 dealt round-robin - only meaningful when every layer's q
                                 is known up front, as in a benchmark of the attention

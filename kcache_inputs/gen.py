@@ -43,6 +43,7 @@ class Workload:
     seed: int
     d: int = 128
     len_range: tuple = None   # (lo, hi) inclusive for ragged batches, None = all S_cap
+    shared_pivots: bool = False   # grouped queries: the heads of a group share pivot positions
 
     @property
     def G(self):
@@ -149,6 +150,8 @@ def pivot_positions(wl, layer, b, h, s_b=None):
         s_b = int(wl.seq_lens()[b])
     n = max(1, int(math.floor(wl.pivot_frac * s_b + 0.5)))
     n = min(n, s_b)
+    if wl.shared_pivots:   # the group's first head decides for the whole group
+        h = (h // wl.G) * wl.G
     rng = np.random.Generator(np.random.Philox(key=_unit_key(wl.seed, _T_PIVOT, layer, b, h)))
     return np.sort(rng.choice(s_b, size=n, replace=False)).astype(np.int64)
 

@@ -14,7 +14,7 @@ GATHER_ZEROCOPY, GATHER_STAGED = 0, 1
 KERNELS = {"kscan": 0, "select": 1, "gather": 2, "store_k": 3, "store_v": 4, "fused": 5,
            "full": 6}
 OPT_PIPELINE_PARTS, OPT_PROFILE, OPT_STAGED_THREADS, OPT_FUSED, OPT_FUSED_ROWS = 0, 1, 2, 3, 4
-OPT_STEP_LANES, OPT_RENORMALIZE, OPT_STEP_SPLIT = 5, 6, 7
+OPT_STEP_LANES, OPT_RENORMALIZE, OPT_STEP_SPLIT, OPT_GQA_DEDUP = 5, 6, 7, 8
 
 _c_i32, _c_i64, _c_p, _c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
 
@@ -273,6 +273,9 @@ class Context:
         self._check(lib().kcache_full_attention(self._h, ctypes.byref(cache.c), _ptr(q), H,
                                                 _ptr(seq_lens), _ptr(out), _stream_ptr(stream)))
         return out
+
+    def set_gqa_dedup(self, on):
+        self.set_option(OPT_GQA_DEDUP, 1 if on else 0)
 
     def set_renormalize(self, on):
         self.set_option(OPT_RENORMALIZE, 1 if on else 0)

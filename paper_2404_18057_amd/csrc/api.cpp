@@ -112,7 +112,7 @@ struct kc_ctx {
   int* flags = nullptr;  // [0] device-check bits, [16] probe sink
   std::string err;
   int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 1,
-      renorm = 0, step_split = 0;
+      renorm = 0, step_split = 0, gqa_dedup = 0;
   int graphs = 0;          // live step graphs: they hold addresses inside ws / counters
   bool capturing = false;  // a step is being captured into a graph: no profiling events
   hipStream_t lane[kMaxLanes] = {};  // streams of kcache_decode_step with more than one lane
@@ -433,6 +433,7 @@ int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, con
   a.renorm = c->renorm;
   a.k_fp8 = cache->k_fp8;
   a.d = cache->d;
+  a.dedup = c->gqa_dedup;
   // 1 / sqrt(d_h), times the cache's 2^k_exp for an 8-bit K cache
   a.scale = ldexpf(inv_sqrt_d(cache->d), cache->k_fp8 ? cache->k_exp : 0);
   KernelTimer t(c, KC_KERNEL_FUSED, st);
@@ -606,6 +607,9 @@ int kcache_set_option(kc_ctx* c, int32_t option, int64_t value) {
       return KC_OK;
     case KC_OPT_FUSED:
       c->fused = value != 0;
+      return KC_OK;
+    case KC_OPT_GQA_DEDUP:
+      c->gqa_dedup = value != 0;
       return KC_OK;
     case KC_OPT_STEP_SPLIT:
       if (value != 0 && value != 1)

@@ -106,6 +106,128 @@ __device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp
   __syncthreads();
 }
 
+// De-duplicated V pull for a group of G query heads (grouped-query attention): the heads
+// of a group read the same V head, so a position that several of them selected is pulled
+// over the host link once and accumulated into each head's output with that head's weight.
+// (The paper says only that the method "applies to ... GQA", section 5; every head still
+// makes its own selection.)  The union is built with a bitmap over the positions:
+//   bm[w]          bit p % 32 of word p / 32 set iff some head kept position p
+//   pf[w]          number of set bits before word w: the rank of a kept position in the
+//                  union is pf[p / 32] + popcount(bits of its word below p)
+//   upos[u]        position of the u-th row of the union (ascending)
+//   wt[u * G + g]  weight of that row for head g, 0 if head g did not keep it
+// idx / w: the group's positions and weights in global memory, [G][N], written earlier by
+// this workgroup.  Needs G * n_eff <= 2 * FT, G * G * n_eff <= 2048 (wt lives in the
+// histogram array), s <= 32 * kFusedZFloats / 2 (bm and pf share the score buffer).
+template <int DT, int G, int D>
+__device__ __forceinline__ void pull_union(const uint4* __restrict__ Vp, const int32_t* idx,
+                                           const float* w, int N, int n_eff, int s,
+                                           float* __restrict__ out_group, Smem<D>* sm) {
+  constexpr int LPR = RowLayout<D>::LPR, RPL = RowLayout<D>::RPL;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sub = lane % LPR, rg = lane / LPR;
+  uint32_t* bm = reinterpret_cast<uint32_t*>(sm->z);
+  int* pf = reinterpret_cast<int*>(sm->z) + kFusedZFloats / 2;
+  float* wt = reinterpret_cast<float*>(sm->sc.hist);
+  int* upos = reinterpret_cast<int*>(sm->sc.list_key);  // list_key, list_idx, list_rank: 1536 ints
+  const int words = (s + 31) >> 5, total = G * n_eff;
+  for (int i = tid; i < words; i += FT) bm[i] = 0u;
+  for (int i = tid; i < total * G; i += FT) wt[i] = 0.f;
+  // the lists were written by whichever threads found the entries: read them around the L1
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  int p[2];
+  float wv[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int e = tid + k * FT;
+    p[k] = -1;
+    wv[k] = 0.f;
+    if (e < total) {
+      const int g = e / n_eff, j = e - g * n_eff;
+      p[k] = ld_dev(idx + (size_t)g * N + j);
+      wv[k] = ld_dev(w + (size_t)g * N + j);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 2; ++k)
+    if (p[k] >= 0) atomicOr(&bm[p[k] >> 5], 1u << (p[k] & 31));
+  __syncthreads();
+  // exclusive prefix of the word popcounts; each thread owns a contiguous run of words
+  const int per = (words + FT - 1) / FT;
+  int mine = 0;
+  for (int i = 0; i < per; ++i) {
+    const int wd = tid * per + i;
+    mine += (wd < words) ? __popc(bm[wd]) : 0;
+  }
+  int before = block_excl_scan<FT>(mine, sm->sc.wave_tot);
+  for (int i = 0; i < per; ++i) {
+    const int wd = tid * per + i;
+    if (wd < words) {
+      pf[wd] = before;
+      before += __popc(bm[wd]);
+    }
+  }
+  if (tid == FT - 1) sm->sc.rank = before;  // rows in the union
+  __syncthreads();
+  const int U = sm->sc.rank;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    if (p[k] >= 0) {
+      const int e = tid + k * FT, g = e / n_eff;
+      const int u = pf[p[k] >> 5] + __popc(bm[p[k] >> 5] & ((1u << (p[k] & 31)) - 1u));
+      wt[u * G + g] = wv[k];
+      upos[u] = p[k];  // every head that kept the row writes the same value
+    }
+  }
+  __syncthreads();
+
+  const int slot = wave * RPL + rg;
+  constexpr int SLOTS = FW * RPL, UNR = 4;
+  float acc[G][8];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[g][i] = 0.f;
+  for (int u0 = slot; u0 < U; u0 += SLOTS * UNR) {
+    uint4 v[UNR];
+    int uu[UNR];
+#pragma unroll
+    for (int k = 0; k < UNR; ++k) {
+      uu[k] = u0 + k * SLOTS;
+      v[k] = make_uint4(0, 0, 0, 0);
+      if (uu[k] < U) v[k] = Vp[(size_t)upos[uu[k]] * LPR + sub];
+    }
+#pragma unroll
+    for (int k = 0; k < UNR; ++k) {
+      if (uu[k] < U) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) fma8<DT>(acc[g], v[k], wt[uu[k] * G + g]);
+      }
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int m = LPR; m < 64; m <<= 1) acc[g][i] += __shfl_xor(acc[g][i], m, 64);
+    }
+    if (rg == 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sm->red_out[wave * D + sub * 8 + i] = acc[g][i];
+    }
+    __syncthreads();
+    if (tid < D) {
+      float t = 0.f;
+#pragma unroll
+      for (int wv_ = 0; wv_ < FW; ++wv_) t += sm->red_out[wv_ * D + tid];
+      out_group[(size_t)g * D + tid] = t;
+    }
+    __syncthreads();
+  }
+}
+
 // Two workgroups per CU (4 waves per SIMD), not the three that registers and LDS
 // would allow: measured on MI355X the launch is 3-7 % faster that way on the
 // large workloads (fewer units in flight per XCD, so units complete and start
@@ -234,6 +356,9 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const bool stage_out = n_eff <= kStage;
   const uint4* __restrict__ Vp =
       reinterpret_cast<const uint4*>(a.V) + kv_phys * a.S_cap * (D / 8);
+  // grouped queries: pull the union of the group's rows once (see pull_union)
+  const bool dedup = G > 1 && a.dedup && G * n_eff <= 2 * FT && G * G * n_eff <= 2048 &&
+                     s <= 32 * (kFusedZFloats / 2);
 #pragma unroll 1
   for (int g = 0; g < G; ++g) {
     const int unit = unit0 + g;
@@ -342,11 +467,17 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     // block_topn ended with a barrier: positions and weights are visible to everyone
     KC_T(f2);
     KC_TADD(5, f2 - f1);
-    pull_and_accumulate<DT, D>(Vp, stage_out ? stage_i : iu, stage_out ? stage_f : wu, n_eff,
-                               a.out + (size_t)unit * D, &sm);
+    if (!dedup)
+      pull_and_accumulate<DT, D>(Vp, stage_out ? stage_i : iu, stage_out ? stage_f : wu, n_eff,
+                                 a.out + (size_t)unit * D, &sm);
     KC_T(f3);
     KC_TADD(6, f3 - f2);
     KC_TADD(8, 1);
+  }
+  if constexpr (G > 1) {
+    if (dedup)
+      pull_union<DT, G, D>(Vp, a.idx + (size_t)unit0 * N, a.w + (size_t)unit0 * N, N, n_eff, s,
+                           a.out + (size_t)unit0 * D, &sm);
   }
 }
 

@@ -88,6 +88,7 @@ struct FusedArgs {
   int kv_split;    // launch units per physical KV head (see kv_split_for)
   int k_fp8;       // 1: K rows are E4M3 codes (128 bytes per row); scale carries 2^k_exp
   int d;           // head dimension: 64, 128 or 256
+  int dedup;       // 1: a group's heads pull the union of their V rows once
   float scale;
 };
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N, int k_row_bytes);
