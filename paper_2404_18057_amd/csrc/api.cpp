@@ -270,7 +270,8 @@ size_t unfused_bytes(size_t units, size_t S_cap, size_t N) {
 // partials, positions and weights.
 size_t fused_bytes(size_t units, size_t chunks_cap, size_t kk, size_t N) {
   return 2 * round256(units * chunks_cap * kk * sizeof(float)) +
-         round256(units * chunks_cap * sizeof(float2)) + 2 * round256(units * N * sizeof(int32_t));
+         round256(units * chunks_cap * sizeof(float2)) + round256(units * chunks_cap * sizeof(float)) +
+         2 * round256(units * N * sizeof(int32_t));
 }
 
 int ensure_staged(kc_ctx* c, size_t rows) {
@@ -415,6 +416,8 @@ int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, con
   p += round256(units * pl.chunks_cap * pl.kk * sizeof(float));
   a.part = reinterpret_cast<float2*>(p);
   p += round256(units * pl.chunks_cap * sizeof(float2));
+  a.bound = reinterpret_cast<float*>(p);
+  p += round256(units * pl.chunks_cap * sizeof(float));
   a.idx = idx_out_dev ? idx_out_dev : reinterpret_cast<int32_t*>(p);
   p += round256(units * N * sizeof(int32_t));
   a.w = w_out_dev ? w_out_dev : reinterpret_cast<float*>(p);

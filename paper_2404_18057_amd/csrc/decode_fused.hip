@@ -294,6 +294,14 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   int32_t* const stage_i = reinterpret_cast<int32_t*>(sm.sc.hist) + kStage;
   const int k_loc = kk < n ? kk : n;
   const bool stage_loc = k_loc <= kStage;
+  // Pruning bound for the merge.  A chunk with more rows than it may keep ("full") also
+  // reports a score that at least r_bound of its rows reach, with r_bound * (number of full
+  // chunks) >= N: the union of those rows alone has N members, so the unit's N-th largest
+  // score is no smaller than the smallest of the reported values, and the merge can drop
+  // every candidate below it before selecting.
+  const int last_rows_b = s - (chunks_b - 1) * R;
+  const int n_full = kk < R ? chunks_b - (last_rows_b > kk ? 0 : 1) : 0;
+  const int r_bound = (G == 1 && n_full > 0 && n > kk) ? (N + n_full - 1) / n_full : 0;
 #pragma unroll 1
   for (int g = 0; g < G; ++g) {
     const float* zg = sm.z + g * R;
@@ -309,6 +317,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     }
     float* cz = a.cand_z + slot * kk;
     int32_t* cp = a.cand_pos + slot * kk;
+    float bound;
     block_topn<FT, false>(key, n, k_loc, &sm.sc, [&](int r, int i, float v) {
       if (stage_loc) {  // collect in LDS, then write whole lines
         stage_f[r] = v;
@@ -317,7 +326,8 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
         st_dev(cz + r, v);
         st_dev(cp + r, row0 + i);
       }
-    });
+    }, r_bound, &bound);
+    if (G == 1 && tid == 0) st_dev(a.bound + slot, bound);
     if (stage_loc) {
       for (int r = tid; r < k_loc; r += FT) {
         st_dev(cz + r, stage_f[r]);
@@ -354,6 +364,9 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const int M = (chunks_b - 1) * kk + (kk < last_rows ? kk : last_rows);  // candidates
   const bool z_in_lds = M <= kFusedZFloats, pos_in_lds = 2 * M <= kFusedZFloats;
   const bool stage_out = n_eff <= kStage;
+  // the merge may prune by the chunks' bounds when everything fits the simple layout
+  // (single-head units only: the grouped-query builds have no registers to spare for it)
+  const bool try_prune = G == 1 && z_in_lds && stage_out && n_full > 0;
   const uint4* __restrict__ Vp =
       reinterpret_cast<const uint4*>(a.V) + kv_phys * a.S_cap * (D / 8);
   // grouped queries: pull the union of the group's rows once (see pull_union)
@@ -367,29 +380,36 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     // Everything the merge needs is requested in one batch of bypassing loads.
     const float* cz = a.cand_z + slot0 * kk;
     const int32_t* cp = a.cand_pos + slot0 * kk;
-    // (loads first, uses afterwards: one trip to memory instead of three)
-    constexpr int LB = 8;
+    constexpr int LB = 8, ZR = kFusedZFloats / FT;  // 16 candidates per thread at most
     int32_t* pos_l = reinterpret_cast<int32_t*>(sm.z) + M;
-    float pm = -INFINITY, pl = 0.f;
+    float pm = -INFINITY, pl = 0.f, pb = INFINITY;
     if (tid < chunks_b) {
       pm = ld_dev(&a.part[slot0 + tid].x);
       pl = ld_dev(&a.part[slot0 + tid].y);
+      if (try_prune && (tid < chunks_b - 1 || last_rows > kk)) pb = ld_dev(a.bound + slot0 + tid);
     }
-    if (z_in_lds) {
+    float zr[G == 1 ? ZR : 1];  // pruned path: all candidates of the unit in registers, i = j * FT + tid
+    if (G == 1 && try_prune) {
+#pragma unroll
+      for (int j = 0; j < ZR; ++j) {
+        const int i = j * FT + tid;
+        zr[j] = (i < M) ? ld_dev(cz + i) : -INFINITY;
+      }
+    } else if (z_in_lds) {
       for (int i0 = tid; i0 < M; i0 += FT * LB) {
-        float zr[LB];
+        float zt[LB];
         int32_t pr[LB];
 #pragma unroll
         for (int u = 0; u < LB; ++u) {
           const int i = i0 + u * FT;
-          zr[u] = (i < M) ? ld_dev(cz + i) : 0.f;
+          zt[u] = (i < M) ? ld_dev(cz + i) : 0.f;
           pr[u] = (i < M && pos_in_lds) ? ld_dev(cp + i) : 0;
         }
 #pragma unroll
         for (int u = 0; u < LB; ++u) {
           const int i = i0 + u * FT;
           if (i < M) {
-            sm.z[i] = zr[u];
+            sm.z[i] = zt[u];
             if (pos_in_lds) pos_l[i] = pr[u];
           }
         }
@@ -402,33 +422,85 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
       l = (m == mm ? l : l * __expf(m - mm)) + (mc == mm ? lc : lc * __expf(mc - mm));
       m = mm;
     }
-    // full-context softmax normaliser from the chunk partials
-    const float2 mZ = block_merge_stats<FT>(m, l, &sm.sc);  // barriers: LDS copies are visible
+    // full-context softmax normaliser from the chunk partials, and the pruning bound
+    const float3 mZ = block_merge_stats_min<FT>(m, l, pb, &sm.sc);  // barriers inside
     const float mx = mZ.x, inv_Z = 1.f / mZ.y;
     KC_T(f1);
     KC_TADD(4, f1 - t4);
+
+    // Pruned path: candidates below the bound cannot be among the N largest (see r_bound).
+    // The survivors are compacted into LDS in candidate order (which is position order, so
+    // ties still go to the lower position) together with their candidate index.
+    int Mp = M;                                  // entries the selection runs over
+    int32_t* src_l = reinterpret_cast<int32_t*>(sm.z) + kFusedZFloats / 2;
+    bool pruned = false;
+    if constexpr (G == 1) if (try_prune) {
+      const int lane = tid & 63, wave = tid >> 6;
+      const float L = mZ.z > -INFINITY ? mZ.z : -INFINITY;  // NaN or -inf: keep everything
+      int* seg_cnt = sm.sc.list_rank;  // [ZR * FW] kept entries per (j, wave) segment
+      int* seg_base = sm.sc.list_idx;
+      const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+#pragma unroll
+      for (int j = 0; j < ZR; ++j) {
+        const uint64_t b = __ballot(zr[j] >= L);
+        if (lane == 0) seg_cnt[j * FW + wave] = __popcll(b);
+      }
+      __syncthreads();
+      if (wave == 0) {  // exclusive scan over the ZR * FW = 128 segments, two per lane
+        const int c0 = seg_cnt[2 * lane], c1 = seg_cnt[2 * lane + 1];
+        const int inc = wave_incl_scan(c0 + c1, lane);
+        seg_base[2 * lane] = inc - c0 - c1;
+        seg_base[2 * lane + 1] = inc - c1;
+        if (lane == 63) sm.sc.rank = inc;
+      }
+      __syncthreads();
+      Mp = sm.sc.rank;
+      pruned = Mp <= kFusedZFloats / 2;          // scores and candidate indices side by side
+      if (pruned) {
+#pragma unroll
+        for (int j = 0; j < ZR; ++j) {
+          const bool keep = zr[j] >= L;
+          const uint64_t b = __ballot(keep);
+          if (keep) {
+            const int dst = seg_base[j * FW + wave] + __popcll(b & lt_mask);
+            sm.z[dst] = zr[j];
+            src_l[dst] = j * FT + tid;
+          }
+        }
+      } else {  // the bound removed too little: select among all candidates as usual
+        Mp = M;
+#pragma unroll
+        for (int j = 0; j < ZR; ++j) {
+          const int i = j * FT + tid;
+          if (i < M) sm.z[i] = zr[j];
+        }
+      }
+      __syncthreads();
+    }
 
     int32_t* iu = a.idx + (size_t)unit * N;
     float* wu = a.w + (size_t)unit * N;
     // With room in the LDS staging arrays (N_eff <= kStage) the selection writes nothing to
     // global memory: weights and positions are collected in LDS and written out afterwards
-    // in whole lines, and candidate positions that did not fit in LDS beside the scores are
+    // in whole lines, and candidate positions that are not in LDS beside the scores are
     // fetched then, all kept entries in one round trip.
-    const bool pos_later = !pos_in_lds && stage_out;
+    const bool pos_here = pos_in_lds && !try_prune;   // positions were loaded into pos_l
+    const bool pos_later = !pos_here && stage_out;
     float kept = 0.f;  // this thread's share of the kept softmax mass (renormalised variant)
     auto emit = [&](int r, int i, float v) {
       const float w = expf(v - mx) * inv_Z;
       kept += w;
+      const int ci = pruned ? src_l[i] : i;      // index into the unit's candidate arrays
       if (stage_out) {
         stage_f[r] = w;
-        stage_i[r] = pos_in_lds ? pos_l[i] : i;
+        stage_i[r] = pos_here ? pos_l[i] : ci;
       } else {
         wu[r] = w;
-        iu[r] = pos_in_lds ? pos_l[i] : ld_dev(cp + i);
+        iu[r] = pos_here ? pos_l[i] : ld_dev(cp + ci);
       }
     };
     if (z_in_lds)
-      block_topn<FT, true>([&](int i) { return sm.z[i]; }, M, n_eff, &sm.sc, emit);
+      block_topn<FT, true>([&](int i) { return sm.z[i]; }, Mp, n_eff, &sm.sc, emit);
     else  // more candidates than the LDS buffer holds: read them around the L2 every pass
       block_topn<FT, true>([&](int i) { return ld_dev(cz + i); }, M, n_eff, &sm.sc, emit);
     if (stage_out) {

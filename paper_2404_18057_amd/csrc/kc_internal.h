@@ -76,6 +76,7 @@ struct FusedArgs {
   float* cand_z;      // [units][chunks_cap][kk] chunk-local top scores
   int32_t* cand_pos;  // their positions
   float2* part;       // [units][chunks_cap] (max, sum of exp) of each chunk
+  float* bound;       // [units][chunks_cap] a score that r of the chunk's rows reach (pruning)
   int* counters;      // [kv units] arrival tickets, zero between launches
   int* flags;
   int H, Hkv, S_cap, N;

@@ -40,7 +40,8 @@ struct alignas(16) TopNScratch {
   int seg_b[NT / 64];
   float red_m[NT / 64];
   float red_l[NT / 64];
-  int bin, rank, list_cnt;
+  float red_b[NT / 64];
+  int bin, bin2, rank, list_cnt;
   uint32_t thr_key;
   int thr_idx;
 };
@@ -135,9 +136,10 @@ __device__ __forceinline__ int block_excl_scan(int v, int* wave_tot) {
 
 // Finds, counting from the top bin, the bin that holds the k-th largest key:
 // above(D) < k <= above(D) + hist[D].  Leaves D in sc->bin and k - above(D) in
-// sc->rank.  Ends with a barrier.
+// sc->rank; with k2 > 0 also the bin of the k2-th largest key in sc->bin2 (same scan).
+// Ends with a barrier.
 template <int NT, int NBINS>
-__device__ __forceinline__ void find_bin(TopNScratch<NT>* sc, int k) {
+__device__ __forceinline__ void find_bin(TopNScratch<NT>* sc, int k, int k2 = 0) {
   constexpr int PER = NBINS / NT;
   static_assert(NBINS % NT == 0, "bins must divide over the threads");
   const int top = NBINS - 1 - (int)threadIdx.x * PER;  // this thread owns top, top-1, ...
@@ -148,13 +150,16 @@ __device__ __forceinline__ void find_bin(TopNScratch<NT>* sc, int k) {
     mine += c[j];
   }
   int above = block_excl_scan<NT>(mine, sc->wave_tot);
-  if (above < k && k <= above + mine) {
+  const bool has_k = above < k && k <= above + mine;
+  const bool has_k2 = k2 > 0 && above < k2 && k2 <= above + mine;
+  if (has_k || has_k2) {
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-      if (above < k && k <= above + c[j]) {
+      if (has_k && above < k && k <= above + c[j]) {
         sc->bin = top - j;
         sc->rank = k - above;
       }
+      if (has_k2 && above < k2 && k2 <= above + c[j]) sc->bin2 = top - j;
       above += c[j];
     }
   }
@@ -185,6 +190,36 @@ __device__ __forceinline__ float2 block_merge_stats(float m, float l, TopNScratc
     ll += (mw == mm) ? sc->red_l[w] : sc->red_l[w] * __expf(mw - mm);
   }
   return make_float2(mm, ll);
+}
+
+// The same with a third value per thread whose minimum over the block is returned in .z.
+template <int NT>
+__device__ __forceinline__ float3 block_merge_stats_min(float m, float l, float b,
+                                                        TopNScratch<NT>* sc) {
+  const int tid = threadIdx.x;
+  const float wm = wave_max(m);
+  l = wave_sum(m == wm ? l : l * __expf(m - wm));
+  b = wave_min(b);
+  __syncthreads();
+  if ((tid & 63) == 0) {
+    sc->red_m[tid >> 6] = wm;
+    sc->red_l[tid >> 6] = l;
+    sc->red_b[tid >> 6] = b;
+  }
+  __syncthreads();
+  float mm = sc->red_m[0], bb = sc->red_b[0];
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) {
+    mm = fmaxf(mm, sc->red_m[w]);
+    bb = fminf(bb, sc->red_b[w]);
+  }
+  float ll = 0.f;
+#pragma unroll
+  for (int w = 0; w < NT / 64; ++w) {
+    const float mw = sc->red_m[w];
+    ll += (mw == mm) ? sc->red_l[w] : sc->red_l[w] * __expf(mw - mm);
+  }
+  return make_float3(mm, ll, bb);
 }
 
 // Softmax partials of keys(0..n-1): (max, sum of exp(key - max)) to every thread.
@@ -219,9 +254,13 @@ __device__ __forceinline__ float2 block_softmax_stats(Key keys, int n, TopNScrat
 // NORMALIZE: take keys relative to the smallest one (see below).  Worth its extra
 // pass when the scores are a pre-filtered, narrow set (the merge of chunk lists);
 // for the raw scores of a chunk the plain float key space resolves well enough.
+//
+// r2 / bound (optional, only without NORMALIZE): a value that at least r2 of the keys reach,
+// namely the lower edge of the first-level bin that holds the r2-th largest key; -inf when
+// no histogram is built (k == n).  Found by the scan that finds the k-th key's bin.
 template <int NT, bool NORMALIZE, typename Key, typename Emit>
 __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<NT>* sc,
-                                           Emit emit) {
+                                           Emit emit, int r2 = 0, float* bound = nullptr) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int NW = NT / 64, U = 8;
   uint32_t T = 0;        // threshold in normalised key space; with k == n every entry is kept
@@ -233,6 +272,7 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
   // scores at hand instead of the whole float line (a few entries per bin near the
   // threshold instead of hundreds).  The map is strictly increasing, so order and
   // equality of keys are unchanged.
+  if (bound) *bound = -INFINITY;
   uint32_t kmin = 0;
   int lz = 0;
   if (NORMALIZE && k < n) {
@@ -357,10 +397,15 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
         if (i0 + u * NT < n) atomicAdd(&sc->hist[nkey(v[u]) >> 21], 1u);
     }
     __syncthreads();
-    find_bin<NT, 2048>(sc, k);
+    const bool want_bound = !NORMALIZE && r2 > 0;
+    find_bin<NT, 2048>(sc, k, want_bound ? (r2 < k ? r2 : k) : 0);
     const uint32_t d1 = (uint32_t)sc->bin;
     const int k1 = sc->rank;
     const int c1 = (int)sc->hist[d1];
+    if (want_bound) {
+      const uint32_t edge = (uint32_t)sc->bin2 << 21;  // smallest key of that bin
+      *bound = __uint_as_float((edge & 0x80000000u) ? (edge & 0x7fffffffu) : ~edge);
+    }
     if (c1 <= kTopNListCap) {
       resolve_in_list(21, d1, c1, k1);
     } else {
