@@ -43,6 +43,7 @@ constexpr int FT = kFusedThreads;
 constexpr int FW = FT / 64;
 
 constexpr int kStage = 1024;  // entries of each of the two staging arrays inside hist[]
+constexpr int kPruneCands = 2 * kFusedZFloats;  // candidates of a unit the pruned merge can take
 
 template <int D>
 struct Smem {
@@ -364,9 +365,10 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const int M = (chunks_b - 1) * kk + (kk < last_rows ? kk : last_rows);  // candidates
   const bool z_in_lds = M <= kFusedZFloats, pos_in_lds = 2 * M <= kFusedZFloats;
   const bool stage_out = n_eff <= kStage;
-  // the merge may prune by the chunks' bounds when everything fits the simple layout
-  // (single-head units only: the grouped-query builds have no registers to spare for it)
-  const bool try_prune = G == 1 && z_in_lds && stage_out && n_full > 0;
+  // the merge may prune by the chunks' bounds when the candidates fit the registers of the
+  // workgroup, 32 per thread (single-head units only: the grouped-query builds have no
+  // registers to spare for it)
+  const bool try_prune = G == 1 && M <= kPruneCands && stage_out && n_full > 0;
   const uint4* __restrict__ Vp =
       reinterpret_cast<const uint4*>(a.V) + kv_phys * a.S_cap * (D / 8);
   // grouped queries: pull the union of the group's rows once (see pull_union)
@@ -380,7 +382,10 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     // Everything the merge needs is requested in one batch of bypassing loads.
     const float* cz = a.cand_z + slot0 * kk;
     const int32_t* cp = a.cand_pos + slot0 * kk;
-    constexpr int LB = 8, ZR = kFusedZFloats / FT;  // 16 candidates per thread at most
+    // ZH: candidates per thread that the LDS buffer could also hold; the second half of zr
+    // is used (big) only for units with more candidates than that
+    constexpr int LB = 8, ZR = kPruneCands / FT, ZH = kFusedZFloats / FT;
+    const bool big = M > kFusedZFloats;
     int32_t* pos_l = reinterpret_cast<int32_t*>(sm.z) + M;
     float pm = -INFINITY, pl = 0.f, pb = INFINITY;
     if (tid < chunks_b) {
@@ -391,9 +396,16 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     float zr[G == 1 ? ZR : 1];  // pruned path: all candidates of the unit in registers, i = j * FT + tid
     if (G == 1 && try_prune) {
 #pragma unroll
-      for (int j = 0; j < ZR; ++j) {
+      for (int j = 0; j < ZH; ++j) {
         const int i = j * FT + tid;
         zr[j] = (i < M) ? ld_dev(cz + i) : -INFINITY;
+      }
+      if (big) {
+#pragma unroll
+        for (int j = ZH; j < ZR; ++j) {
+          const int i = j * FT + tid;
+          zr[j] = (i < M) ? ld_dev(cz + i) : -INFINITY;
+        }
       }
     } else if (z_in_lds) {
       for (int i0 = tid; i0 < M; i0 += FT * LB) {
@@ -441,24 +453,47 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
       int* seg_base = sm.sc.list_idx;
       const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
-      for (int j = 0; j < ZR; ++j) {
+      for (int j = 0; j < ZH; ++j) {
         const uint64_t b = __ballot(zr[j] >= L);
         if (lane == 0) seg_cnt[j * FW + wave] = __popcll(b);
       }
+      if (big) {
+#pragma unroll
+        for (int j = ZH; j < ZR; ++j) {
+          const uint64_t b = __ballot(zr[j] >= L);
+          if (lane == 0) seg_cnt[j * FW + wave] = __popcll(b);
+        }
+      }
       __syncthreads();
-      if (wave == 0) {  // exclusive scan over the ZR * FW = 128 segments, two per lane
-        const int c0 = seg_cnt[2 * lane], c1 = seg_cnt[2 * lane + 1];
-        const int inc = wave_incl_scan(c0 + c1, lane);
-        seg_base[2 * lane] = inc - c0 - c1;
-        seg_base[2 * lane + 1] = inc - c1;
-        if (lane == 63) sm.sc.rank = inc;
+      if (wave == 0) {
+        if (!big) {  // exclusive scan over the ZH * FW = 128 segments, two per lane
+          const int c0 = seg_cnt[2 * lane], c1 = seg_cnt[2 * lane + 1];
+          const int inc = wave_incl_scan(c0 + c1, lane);
+          seg_base[2 * lane] = inc - c0 - c1;
+          seg_base[2 * lane + 1] = inc - c1;
+          if (lane == 63) sm.sc.rank = inc;
+        } else {     // ZR * FW = 256 segments, four per lane
+          int c[4], sum = 0;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            c[q] = seg_cnt[4 * lane + q];
+            sum += c[q];
+          }
+          const int inc = wave_incl_scan(sum, lane);
+          int before = inc - sum;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            seg_base[4 * lane + q] = before;
+            before += c[q];
+          }
+          if (lane == 63) sm.sc.rank = inc;
+        }
       }
       __syncthreads();
       Mp = sm.sc.rank;
       pruned = Mp <= kFusedZFloats / 2;          // scores and candidate indices side by side
       if (pruned) {
-#pragma unroll
-        for (int j = 0; j < ZR; ++j) {
+        auto place = [&](int j) {
           const bool keep = zr[j] >= L;
           const uint64_t b = __ballot(keep);
           if (keep) {
@@ -466,13 +501,21 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
             sm.z[dst] = zr[j];
             src_l[dst] = j * FT + tid;
           }
+        };
+#pragma unroll
+        for (int j = 0; j < ZH; ++j) place(j);
+        if (big) {
+#pragma unroll
+          for (int j = ZH; j < ZR; ++j) place(j);
         }
       } else {  // the bound removed too little: select among all candidates as usual
         Mp = M;
+        if (z_in_lds) {
 #pragma unroll
-        for (int j = 0; j < ZR; ++j) {
-          const int i = j * FT + tid;
-          if (i < M) sm.z[i] = zr[j];
+          for (int j = 0; j < ZH; ++j) {
+            const int i = j * FT + tid;
+            if (i < M) sm.z[i] = zr[j];
+          }
         }
       }
       __syncthreads();
@@ -499,7 +542,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
         iu[r] = pos_here ? pos_l[i] : ld_dev(cp + ci);
       }
     };
-    if (z_in_lds)
+    if (pruned || z_in_lds)
       block_topn<FT, true>([&](int i) { return sm.z[i]; }, Mp, n_eff, &sm.sc, emit);
     else  // more candidates than the LDS buffer holds: read them around the L2 every pass
       block_topn<FT, true>([&](int i) { return ld_dev(cz + i); }, M, n_eff, &sm.sc, emit);
@@ -587,17 +630,19 @@ hipError_t launch_d(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
 // larger chunks mean fewer workgroups paying the fixed selection and hand-over
 // cost, and fewer candidates to merge.  Measured on MI355X, 256 KiB of K per workgroup
 // (1024 rows of 16-bit values, 2048 rows of 8-bit codes) is the sweet spot
-// as long as all of a unit's candidates fit the merging workgroup's LDS buffer,
-// ceil(S/R) * min(N, R) <= kFusedZFloats; otherwise the smallest R that fits.
+// as long as all of a unit's candidates fit the merging workgroup, ceil(S/R) * min(N, R) <=
+// kFusedZFloats (its LDS buffer; twice that for single-head units with N <= 1024, whose merge
+// first drops most candidates from registers); otherwise the smallest R that fits.
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N, int k_row_bytes) {
   const int cap = kFusedZFloats / G;
+  const int64_t cands = (G == 1 && N <= kStage) ? kPruneCands : kFusedZFloats;
+  const auto fits = [&](int r) { return (int64_t)((S_cap + r - 1) / r) * (N < r ? N : r) <= cands; };
   // the same K bytes per workgroup whatever the row size: an 8-bit K cache takes 2048 rows
   int R = 1024 * kRowBytes / k_row_bytes;  // 512 rows of 512 bytes ... 2048 rows of 128 bytes
-  while (R < cap && (int64_t)((S_cap + R - 1) / R) * (N < R ? N : R) > kFusedZFloats) R *= 2;
+  while (R < cap && !fits(R)) R *= 2;
   if (R > cap) R = cap;
   // small problems: more, smaller workgroups as long as the merge still fits
-  while (R > kFusedThreads && (int64_t)kv_units * ((S_cap + R - 1) / R) < 512 &&
-         (int64_t)((S_cap + R / 2 - 1) / (R / 2)) * (N < R / 2 ? N : R / 2) <= kFusedZFloats)
+  while (R > kFusedThreads && (int64_t)kv_units * ((S_cap + R - 1) / R) < 512 && fits(R / 2))
     R /= 2;
   return R;
 }
