@@ -398,10 +398,31 @@ def test_seeded_random_shapes(kc, ctx, case):
     check_manual(res, lens, N, G=G)
 
 
+def test_many_tied_candidates_defeat_the_pruning(kc, ctx):
+    """40 000 positions, N = 512, two score levels: 100 scattered positions score high, all the
+    others tie.  The unit brings 20 x 512 candidates, more than the merging workgroup's LDS
+    buffer holds; every chunk reports the tied score as its edge, so nothing can be dropped
+    and the selection has to run over the lists in memory, breaking the tie by position."""
+    rng = np.random.default_rng(77)
+    S, d, N = 40_000, 128, 512
+    base = rng.standard_normal(d)
+    q = base[None, None, :]
+    hi = np.sort(rng.choice(S, size=100, replace=False))
+    level = np.zeros(S)
+    level[hi] = 1.0
+    K = ((0.25 + level[:, None]) * base[None, :] / 4.0)[None, None]
+    V = rng.standard_normal((1, 1, S, d))
+    out, idx, w, _ = res = manual_case(kc, ctx, q, K, V, [S], N)
+    rest = np.setdiff1d(np.arange(S), hi)[:N - len(hi)]
+    assert idx[0, 0].tolist() == sorted(hi.tolist() + rest.tolist())
+    check_manual(res, [S], N)
+
+
 def test_context_too_long_for_the_merge_buffer(kc, ctx):
     """300 000 positions with N = 256: even at the largest chunk size the unit's candidates
-    (37 x 256) exceed the merging workgroup's LDS buffer, so the merge reads them from memory
-    on every pass.  Two heads, one of them with duplicated rows across distant chunks."""
+    (37 x 256) exceed the merging workgroup's LDS buffer; they are judged against the chunks'
+    edges in registers, and only the survivors are selected from.  Two heads, one of them
+    with duplicated rows across distant chunks."""
     rng = np.random.default_rng(31)
     S, N = 300_000, 256
     q = rng.standard_normal((1, 2, 128))
