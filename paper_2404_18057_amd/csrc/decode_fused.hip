@@ -433,6 +433,9 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
       const float mm = fmaxf(m, mc);
       l = (m == mm ? l : l * __expf(m - mm)) + (mc == mm ? lc : lc * __expf(mc - mm));
       m = mm;
+      if constexpr (G == 1)
+        if (try_prune && (c < chunks_b - 1 || last_rows > kk))
+          pb = fminf(pb, ld_dev(a.bound + slot0 + c));
     }
     // full-context softmax normaliser from the chunk partials, and the pruning bound
     const float3 mZ = block_merge_stats_min<FT>(m, l, pb, &sm.sc);  // barriers inside

@@ -418,6 +418,19 @@ def test_many_tied_candidates_defeat_the_pruning(kc, ctx):
     check_manual(res, [S], N)
 
 
+def test_more_chunks_than_threads_in_the_merging_workgroup(kc, ctx):
+    """600 000 positions with N = 8: 586 chunks of 1024 rows, more than the 512 threads that
+    each fetch one chunk's partials and edge in the first round."""
+    rng = np.random.default_rng(32)
+    S, N = 600_000, 8
+    q = rng.standard_normal((1, 1, 128)).astype(np.float32)
+    K = rng.standard_normal((1, 1, S, 128)).astype(np.float32)
+    V = rng.standard_normal((1, 1, S, 128)).astype(np.float32)
+    K[0, 0, 599_990] = K[0, 0, 5]                       # an exact tie between the ends
+    res = manual_case(kc, ctx, q, K, V, [S], N)
+    check_manual(res, [S], N)
+
+
 def test_context_too_long_for_the_merge_buffer(kc, ctx):
     """300 000 positions with N = 256: even at the largest chunk size the unit's candidates
     (37 x 256) exceed the merging workgroup's LDS buffer; they are judged against the chunks'
