@@ -212,6 +212,10 @@ int kcache_prefill_store(kc_ctx* ctx, const kc_layer_cache* cache, const void* k
  *   gather_mode   kc_gather_mode
  *   stream        hipStream_t; all results are complete in stream order
  * Scores and softmax are fp32; the selection is made on the fp32 scores.
+ * Non-finite inputs: a NaN or infinity in q, K or V makes out / w_out of the units
+ * it reaches unspecified (NaN as a rule), but never unsafe: every position in
+ * idx_out stays in [-1, s_b), exactly N_eff of them are kept, and no row outside the
+ * unit's cache is read.
  * A layer with cache->v_in_hbm is accepted too (its N rows then come from HBM);
  * KC_GATHER_STAGED is KC_ERR_UNSUPPORTED for such a layer.  Head dimensions 64 and
  * 256 and 8-bit K caches are served by the fused zero-copy path only (KC_OPT_FUSED

@@ -1160,9 +1160,11 @@ int kcache_device_check(kc_ctx* c) {
   KC_HIP(c, hipMemcpy(&host_flags, c->flags, sizeof(int), hipMemcpyDeviceToHost));
   if (host_flags == 0) return KC_OK;
   KC_HIP(c, hipMemset(c->flags, 0, sizeof(int)));
-  return fail(c, KC_ERR_DEVICE_CHECK, "device check:%s%s",
+  return fail(c, KC_ERR_DEVICE_CHECK, "device check:%s%s%s",
               (host_flags & kc::kFlagBadSeqLen) ? " seq_lens outside [1, S_cap]" : "",
-              (host_flags & kc::kFlagBadPos) ? " store position outside [0, S_cap)" : "");
+              (host_flags & kc::kFlagBadPos) ? " store position outside [0, S_cap)" : "",
+              (host_flags & kc::kFlagBadIndex) ? " a selected position fell outside its sequence "
+                                                 "(skipped, not read)" : "");
 }
 
 int kcache_profile_read(kc_ctx* c, int32_t kernel, double* total_ms, int64_t* launches) {

@@ -25,8 +25,8 @@
 //
 // Units finish at different times (chunks of one unit are adjacent in the
 // grid), so the V pulls of early units overlap the K scan of later ones.
-#include "attn_common.cuh"
-#include "topn.cuh"
+#include "attn_common.h"
+#include "topn.h"
 
 namespace kc {
 namespace {
@@ -58,7 +58,7 @@ struct Smem {
 // iu / wu may point to LDS or to global memory.
 template <int DT, int D>
 __device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp, const int32_t* iu,
-                                                    const float* wu, int n_eff,
+                                                    const float* wu, int n_eff, int s, int* flags,
                                                     float* __restrict__ out_u, Smem<D>* sm) {
   constexpr int LPR = RowLayout<D>::LPR, RPL = RowLayout<D>::RPL;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -77,6 +77,11 @@ __device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp
       const int j = j0 + u * SLOTS;
       t[u] = (j < n_eff) ? iu[j] : -1;
       w[u] = (j < n_eff) ? wu[j] : 0.f;
+      // the selection only emits positions below s; a row outside the unit is never read
+      if (t[u] >= s) {
+        atomicOr(flags, kFlagBadIndex);
+        t[u] = -1;
+      }
     }
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
@@ -148,6 +153,7 @@ __device__ __forceinline__ void pull_union(const uint4* __restrict__ Vp, const i
       const int g = e / n_eff, j = e - g * n_eff;
       p[k] = ld_dev(idx + (size_t)g * N + j);
       wv[k] = ld_dev(w + (size_t)g * N + j);
+      if (p[k] >= s) p[k] = -1;  // cannot happen for a finished selection; never index past s
     }
   }
 #pragma unroll
@@ -494,7 +500,10 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
       }
       __syncthreads();
       Mp = sm.sc.rank;
-      pruned = Mp <= kFusedZFloats / 2;          // scores and candidate indices side by side
+      // scores and candidate indices side by side in LDS.  Fewer survivors than entries to
+      // keep can only happen when scores are NaN (they compare false against the bound): the
+      // ordinary selection below orders by key, NaN included, and always keeps n_eff entries.
+      pruned = Mp <= kFusedZFloats / 2 && Mp >= n_eff;
       if (pruned) {
         auto place = [&](int j) {
           const bool keep = zr[j] >= L;
@@ -552,8 +561,8 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     if (stage_out) {
       for (int r = tid; r < n_eff; r += FT) {
         int32_t t = stage_i[r];
-        if (pos_later) {
-          t = ld_dev(cp + t);
+        if (pos_later) {  // t is an index into the unit's candidate arrays
+          t = ((unsigned)t < (unsigned)M) ? ld_dev(cp + t) : -1;
           stage_i[r] = t;
         }
         iu[r] = t;
@@ -587,7 +596,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     KC_TADD(5, f2 - f1);
     if (!dedup)
       pull_and_accumulate<DT, D>(Vp, stage_out ? stage_i : iu, stage_out ? stage_f : wu, n_eff,
-                                 a.out + (size_t)unit * D, &sm);
+                                 s, a.flags, a.out + (size_t)unit * D, &sm);
     KC_T(f3);
     KC_TADD(6, f3 - f2);
     KC_TADD(8, 1);

@@ -15,8 +15,8 @@
 //   4. (m, l, o) go to the workspace; the workgroup that completes a unit rescales
 //      and adds the chunk results:  out = sum_c e^(m_c - M) o_c / sum_c e^(m_c - M) l_c.
 // HBM bound: 512 bytes and 4 G d_h FLOPs per (KV head, position).
-#include "attn_common.cuh"
-#include "topn.cuh"
+#include "attn_common.h"
+#include "topn.h"
 
 namespace kc {
 namespace {

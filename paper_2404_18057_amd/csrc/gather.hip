@@ -8,30 +8,10 @@
 // up to 128 outstanding 256-byte reads per workgroup, and every other resident
 // workgroup adds its own.  The rows are read straight out of mapped, pinned
 // host memory; nothing is staged in HBM.
-#include "kc_internal.h"
+#include "attn_common.h"
 
 namespace kc {
 namespace {
-
-template <int DT>
-__device__ __forceinline__ void fma8(float (&acc)[8], const uint4& v, float w) {
-  const uint32_t r[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    float lo, hi;
-    if constexpr (DT == 0) {
-      typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-      half2_t h = __builtin_bit_cast(half2_t, r[i]);
-      lo = (float)h.x;
-      hi = (float)h.y;
-    } else {
-      lo = __uint_as_float(r[i] << 16);
-      hi = __uint_as_float(r[i] & 0xffff0000u);
-    }
-    acc[2 * i] = fmaf(w, lo, acc[2 * i]);
-    acc[2 * i + 1] = fmaf(w, hi, acc[2 * i + 1]);
-  }
-}
 
 template <int DT>
 __global__ __launch_bounds__(256) void gather_kernel(const uint16_t* __restrict__ V,
@@ -66,6 +46,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint16_t* __restrict_
       const int j = j0 + u * 16;
       t[u] = (j < N) ? iu[j] : -1;  // -1 marks the padding beyond N_eff
       w[u] = (j < N) ? wu[j] : 0.f;
+      if (t[u] >= S_cap) t[u] = -1;  // a position outside the cache is never read
       if (packed && t[u] >= 0) t[u] = j;
     }
     if (t[0] < 0) break;  // positions are ascending with the padding at the end

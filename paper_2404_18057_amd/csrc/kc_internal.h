@@ -24,6 +24,7 @@ __device__ __forceinline__ uint4 load_stream16(const uint4* p) {
 // bits of the device-check word
 constexpr int kFlagBadSeqLen = 1;
 constexpr int kFlagBadPos = 2;
+constexpr int kFlagBadIndex = 4;  // a selected position fell outside [0, s): skipped, never read
 
 // The kernels score at most 8 query heads from one pass over a K row.  Larger groups
 // (16 or 32 query heads per KV head) run as 2 or 4 launch units per KV head, each with 8 of

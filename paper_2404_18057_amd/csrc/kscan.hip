@@ -12,47 +12,10 @@
 //     first use, which is what keeps enough bytes in flight per CU;
 //   * the G query heads that share a KV head are scored from the same
 //     registers, so each K row is read from HBM exactly once per group.
-#include "kc_internal.h"
+#include "attn_common.h"
 
 namespace kc {
 namespace {
-
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-typedef __bf16 bf162_t __attribute__((ext_vector_type(2)));
-
-template <int DT>
-__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
-  if constexpr (DT == 0) {
-    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b),
-                                  acc, false);
-  } else {
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf162_t, a),
-                                           __builtin_bit_cast(bf162_t, b), acc, false);
-  }
-}
-
-template <int DT>
-__device__ __forceinline__ float dot8(const uint4& k, const uint4& q) {
-  float a = dot2<DT>(k.x, q.x, 0.f);
-  a = dot2<DT>(k.y, q.y, a);
-  a = dot2<DT>(k.z, q.z, a);
-  return dot2<DT>(k.w, q.w, a);
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true);
-  return x + __builtin_bit_cast(float, y);
-}
-
-// Sum over the 16 lanes of a DPP row; every lane ends with the total.
-__device__ __forceinline__ float row16_sum(float x) {
-  x = dpp_add<0xB1>(x);   // quad_perm [1,0,3,2]
-  x = dpp_add<0x4E>(x);   // quad_perm [2,3,0,1]
-  x = dpp_add<0x141>(x);  // row_half_mirror
-  x = dpp_add<0x140>(x);  // row_mirror
-  return x;
-}
 
 template <int DT, int G>
 __global__ __launch_bounds__(256) void kscan_kernel(const uint16_t* __restrict__ q,
@@ -112,7 +75,7 @@ __global__ __launch_bounds__(256) void kscan_kernel(const uint16_t* __restrict__
     for (int u = 0; u < 16; ++u) {
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float a = row16_sum(dot8<DT>(kr[u], qv[g]));
+        float a = row_sum<16>(dot8<DT>(kr[u], qv[g]));
         keep[g] = (sub == u) ? a : keep[g];
       }
     }

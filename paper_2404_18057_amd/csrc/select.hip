@@ -1,13 +1,12 @@
 // Softmax statistics and exact top-N selection for one (sequence, query head)
 // unit per workgroup, from scores that a separate K-scan launch left in HBM
-// (paper section 3.1: "After the softmax operation, TopN selects the N most
-// relevant results"; Table 1 row S~).  Used by the unfused path (staged gather,
+// (paper section 3.1; Table 1 row S~).  Used by the unfused path (staged gather,
 // per-kernel measurements); the fused decode kernel selects on chip.
 //
 // exp is strictly increasing, so the N largest softmax values sit at the N
-// largest scores: the selection runs on the fp32 scores (see topn.cuh).
+// largest scores: the selection runs on the fp32 scores (see topn.h).
 #include "kc_internal.h"
-#include "topn.cuh"
+#include "topn.h"
 
 namespace kc {
 namespace {

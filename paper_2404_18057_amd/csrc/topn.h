@@ -1,5 +1,5 @@
-// Block-wide exact top-k selection over fp32 scores (paper section 3.1: "TopN
-// selects the N most relevant results").
+// Block-wide exact top-k selection over fp32 scores (paper section 3.1; Table 1
+// row S~: the N largest softmax entries of a (sequence, head) are kept).
 //
 // Scores are mapped to unsigned keys whose integer order is the float order and
 // ordered by (key descending, index ascending): "largest first, lower index on
@@ -263,6 +263,12 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
                                            Emit emit, int r2 = 0, float* bound = nullptr) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int NW = NT / 64, U = 8;
+  if (bound) *bound = -INFINITY;
+  if (k > n) k = n;      // never more than there is (callers pass k <= n; this keeps a
+  if (k <= 0) {          // miscounted caller from reading the scratch of an empty selection)
+    __syncthreads();
+    return;
+  }
   uint32_t T = 0;        // threshold in normalised key space; with k == n every entry is kept
   int T_idx = 0x7fffffff;
   int take_eq = -1;      // >= 0 only on the fallback path: entries == T kept in index order
@@ -272,7 +278,6 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
   // scores at hand instead of the whole float line (a few entries per bin near the
   // threshold instead of hundreds).  The map is strictly increasing, so order and
   // equality of keys are unchanged.
-  if (bound) *bound = -INFINITY;
   uint32_t kmin = 0;
   int lz = 0;
   if (NORMALIZE && k < n) {

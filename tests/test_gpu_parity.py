@@ -333,6 +333,41 @@ def test_bad_arguments_are_reported_not_fatal(kc, ctx):
     assert e.value.status == -6
 
 
+def test_non_finite_scores_never_leave_the_sequence(kc, ctx):
+    """A NaN in q makes every score of that head NaN; NaN rows in K make some scores of another
+    head NaN (enough of them in one chunk to turn its pruning edge into NaN).  The results of
+    those units are unspecified, but every kept position must lie inside the sequence, exactly
+    N_eff of them are kept, no row outside the cache is read (device check clean), and the
+    heads that saw only finite values still match the oracle."""
+    rng = np.random.default_rng(123)
+    B, H, S, d, N = 2, 4, 9000, 128, 64     # 9 chunks of 1024: the pruned merge runs
+    q = rng.standard_normal((B, H, d)).astype(np.float32)
+    K = rng.standard_normal((B, H, S, d)).astype(np.float32)
+    V = rng.standard_normal((B, H, S, d)).astype(np.float32)
+    q[0, 1, 5] = np.nan                      # head (0, 1): all scores NaN
+    K[0, 2, 2048:2048 + 40, 7] = np.nan      # head (0, 2): 40 NaN scores in the third chunk
+    K[1, 0, 100, 0] = np.inf                 # head (1, 0): one infinite score
+    lens = [S, 4500]
+    out, idx, w, (qb, kb, vb, code) = manual_case(kc, ctx, q, K, V, lens, N)   # runs device_check
+    for b in range(B):
+        s = lens[b]
+        for h in range(H):
+            kept = idx[b, h]
+            assert ((kept >= 0) & (kept < s)).all(), "position outside the sequence at (%d,%d)" % (b, h)
+            assert len(set(kept.tolist())) == N, "positions not distinct at (%d,%d)" % (b, h)
+            if (b, h) in ((0, 1), (0, 2), (1, 0)):
+                continue
+            r = oracle.decode_unit(qb[b, h], kb[b, h, :s], vb[b, h, :s], code, N, want_scores=True)
+            r["v"] = oracle.decode16(vb[b, h, :s], code)
+            check_unit(r, N, out[b, h], idx[b, h], w[b, h], tag="finite head (%d,%d)" % (b, h))
+    # the same launch shape with finite inputs afterwards: nothing was left behind
+    q[0, 1, 5] = 0.5
+    K[0, 2, 2048:2048 + 40, 7] = 0.25
+    K[1, 0, 100, 0] = 1.0
+    res = manual_case(kc, ctx, q, K, V, lens, N)
+    check_manual(res, lens, N)
+
+
 # ------------------------------------------------------------------ renormalised variant
 @pytest.mark.parametrize("gather_mode", [0, 1])
 def test_renormalised_variant_matches_its_oracle(kc, ctx, gather_mode):
