@@ -32,7 +32,9 @@
  * uniform-score closed form, two-score logistic closed form, GQA by head
  * repetition, ragged batch by independent calls, 16-bit decode against a
  * library decode; the conventional-attention routine against the same library
- * routine, a uniform-score closed form and the N = s case of the top-N routine.
+ * routine, a uniform-score closed form and the N = s case of the top-N routine;
+ * the cache store (both forms) bit for bit against a slice assignment of rows with
+ * distinct elements.
  * The no-renormalisation reading itself is "parity unpinned"
  * by the paper: only the literal formula fixes it.
  */

@@ -46,6 +46,11 @@ MUTANTS = [
     ("k8 store: V quantised position", "k8_cache[dst] = kco_double_to_e4m3(ldexp(kco_decode(k_new[src], dtype), -k_exp));", "k8_cache[dst] = kco_double_to_e4m3(ldexp(kco_decode(v_new[src], dtype), -k_exp));"),
     ("store: heads and tokens swapped in the source index", "size_t src = (((size_t)b * T + t) * Hkv + hk) * d + c;\n          size_t dst = (((size_t)b * Hkv + hk) * S_cap + (size_t)(pos[b] + t)) * d + c;\n          k_cache[dst] = k_new[src];", "size_t src = (((size_t)b * Hkv + hk) * T + t) * d + c;\n          size_t dst = (((size_t)b * Hkv + hk) * S_cap + (size_t)(pos[b] + t)) * d + c;\n          k_cache[dst] = k_new[src];"),
     ("store: position offset ignored", "(size_t)(pos[b] + t)) * d + c;\n          k_cache[dst] = k_new[src];", "(size_t)(t)) * d + c;\n          k_cache[dst] = k_new[src];"),
+    ("store: tokens reversed inside the range", "size_t dst = (((size_t)b * Hkv + hk) * S_cap + (size_t)(pos[b] + t)) * d + c;\n          k_cache[dst] = k_new[src];",
+     "size_t dst = (((size_t)b * Hkv + hk) * S_cap + (size_t)(pos[b] + (T - 1 - t))) * d + c;\n          k_cache[dst] = k_new[src];"),
+    ("k8 store: tokens reversed inside the range", "size_t dst = (((size_t)b * Hkv + hk) * S_cap + (size_t)(pos[b] + t)) * d + c;\n          k8_cache[dst] =",
+     "size_t dst = (((size_t)b * Hkv + hk) * S_cap + (size_t)(pos[b] + (T - 1 - t))) * d + c;\n          k8_cache[dst] ="),
+    ("store: V rows written into the K cache's place", "k_cache[dst] = k_new[src];\n          v_cache[dst] = v_new[src];", "k_cache[dst] = v_new[src];\n          v_cache[dst] = k_new[src];"),
     ("conventional attention: scale dropped", "const double inv_sqrt_d = 1.0 / sqrt((double)d);\n  for (int32_t t = 0; t < s; ++t) {\n    double acc = 0.0;\n    for (int32_t c = 0; c < d; ++c)\n      acc += kco_decode(q[c], dtype)",
      "const double inv_sqrt_d = 1.0;\n  for (int32_t t = 0; t < s; ++t) {\n    double acc = 0.0;\n    for (int32_t c = 0; c < d; ++c)\n      acc += kco_decode(q[c], dtype)"),
     ("conventional attention: not normalised", "const double p = exp(z[t] - m) / Z;", "const double p = exp(z[t] - m);"),

@@ -337,6 +337,41 @@ def test_store_then_full_attention_equals_library_attention_on_token_major_tenso
     assert (kc[1, :, T:] == 0).all() and (vc[0, :, 4 + T:] == 0).all()
 
 
+def test_store_places_every_row_where_a_slice_assignment_does():
+    # Direct pin of the placement (Figure 1, upper half: a layer's new K / V rows are appended
+    # to its caches).  Every element of the new rows is a distinct bit pattern, the expected
+    # caches are written by numpy slice assignment of the transposed [Hkv][T][d] block at
+    # [pos, pos + T), and the comparison is bit for bit: a reversed, shifted or transposed
+    # placement inside the range changes at least one element.  Attention over the whole
+    # cache cannot see such a permutation when K and V are permuted alike; this test can.
+    rng = np.random.default_rng(170)
+    B, T, Hkv, d, S_cap = 3, 7, 2, 8, 19
+    n = B * T * Hkv * d
+    k_new = rng.permutation(n).astype(np.uint16).reshape(B, T, Hkv, d)            # 0 .. n-1
+    v_new = (rng.permutation(n) + 20000).astype(np.uint16).reshape(B, T, Hkv, d)  # disjoint from K
+    pos = np.array([0, 12, 5], np.int32)            # start, flush with the end, in the middle
+    kc = np.full((B, Hkv, S_cap, d), 0xAAAA, np.uint16)
+    vc = np.full((B, Hkv, S_cap, d), 0x5555, np.uint16)
+    want_k, want_v = kc.copy(), vc.copy()
+    for b in range(B):
+        want_k[b, :, pos[b]:pos[b] + T, :] = k_new[b].transpose(1, 0, 2)
+        want_v[b, :, pos[b]:pos[b] + T, :] = v_new[b].transpose(1, 0, 2)
+    oracle.store(kc, vc, k_new, v_new, pos)
+    assert np.array_equal(kc, want_k)
+    assert np.array_equal(vc, want_v)
+    # the 8-bit K variant places rows the same way: V bit for bit, K as the codes of the
+    # slice-assigned rows (distinct small values, so that codes differ between neighbours)
+    k_vals = bits((rng.permutation(n).reshape(B, T, Hkv, d) % 97 - 48) / 8.0)
+    k8 = np.full((B, Hkv, S_cap, d), 0x7F, np.uint8)
+    v8 = np.full((B, Hkv, S_cap, d), 0x5555, np.uint16)
+    oracle.store_k8(k8, v8, k_vals, v_new, pos, F16, 0)
+    want_k8 = np.full((B, Hkv, S_cap, d), 0x7F, np.uint8)
+    for b in range(B):
+        want_k8[b, :, pos[b]:pos[b] + T, :] = oracle.e4m3_quantise(k_vals[b].transpose(1, 0, 2), F16, 0)
+    assert np.array_equal(k8, want_k8)
+    assert np.array_equal(v8, want_v)
+
+
 def test_store_rejects_overflowing_positions():
     kc = np.zeros((1, 1, 4, 8), np.uint16)
     vc = np.zeros((1, 1, 4, 8), np.uint16)
