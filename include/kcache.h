@@ -227,6 +227,31 @@ int kcache_decode_attention(kc_ctx* ctx, const kc_layer_cache* cache, const void
                             void* stream);
 
 /*
+ * kcache_decode_attention for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * kernels and results as kcache_decode_attention with KC_GATHER_ZEROCOPY on the fused
+ * path, but the launch's scratch (chunk candidates, partials, arrival tickets) is a
+ * fixed array inside the library's code object instead of the context's workspace,
+ * and the call performs no hipMalloc / hipFree / event creation and no host
+ * synchronisation.  Every GPU the library runs on holds its own copy of the array
+ * until the process ends.
+ *   - limit: the fused launch of the shape must need no more than
+ *     kcache_static_scratch_bytes() (48 MiB) of scratch and at most 16384 (sequence,
+ *     KV head) units; beyond that the call returns KC_ERR_WORKSPACE and enqueues
+ *     nothing.  (Config 2's layer needs 17 MiB, config 4's at N = 128 34 MiB.)
+ *   - all calls on one GPU share that GPU's array, whichever context or stream they
+ *     come from: calls that overlap in time on one GPU race.  Calls on one stream are
+ *     ordered and safe.  The tickets are cleared by a small kernel at the start of
+ *     every call, so a previous call's leftovers do not matter.
+ *   - KC_OPT_PROFILE does not time this call; KC_OPT_FUSED is ignored (always fused).
+ */
+int kcache_decode_attention_static(kc_ctx* ctx, const kc_layer_cache* cache, const void* q_dev,
+                                   int32_t H, const int32_t* seq_lens_dev, int32_t N,
+                                   float* out_dev, int32_t* idx_out_dev, float* w_out_dev,
+                                   void* stream);
+size_t kcache_static_scratch_bytes(void);
+
+/*
  * Conventional decode attention for one layer whose V cache is in HBM
  * (cache->v_in_hbm == 1):  out = softmax(q K^T / sqrt(d_h)) V over all s_b cached
  * positions (section 2; Table 1, rows S and A of plain MHA).  This is what the

@@ -5,9 +5,9 @@ of the method runs in the HIP kernels behind the C ABI of include/kcache.h.
 There is no CPU fallback: loading fails loudly when the library is missing.
 """
 from .binding import (KC_F16, KC_BF16, GATHER_ZEROCOPY, GATHER_STAGED, KERNELS, KCacheError,
-                      Context, LayerCache, StepGraph, lib, lib_path, workspace_bytes, check_shapes, version,
-                      declared_symbols)
+                      Context, LayerCache, StepGraph, lib, lib_path, workspace_bytes, static_scratch_bytes,
+                      check_shapes, version, declared_symbols)
 
 __all__ = ["KC_F16", "KC_BF16", "GATHER_ZEROCOPY", "GATHER_STAGED", "KERNELS", "KCacheError",
-           "Context", "LayerCache", "StepGraph", "lib", "lib_path", "workspace_bytes", "check_shapes",
+           "Context", "LayerCache", "StepGraph", "lib", "lib_path", "workspace_bytes", "static_scratch_bytes", "check_shapes",
            "version", "declared_symbols"]

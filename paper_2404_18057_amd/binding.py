@@ -67,6 +67,9 @@ def lib():
                                                     _c_p]),
             "kcache_decode_attention": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_i32, _c_p, _c_i32,
                                                        _c_p, _c_p, _c_p, _c_i32, _c_p]),
+            "kcache_decode_attention_static": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_i32, _c_p,
+                                                              _c_i32, _c_p, _c_p, _c_p, _c_p]),
+            "kcache_static_scratch_bytes": (_c_sz, []),
             "kcache_full_attention": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_i32, _c_p, _c_p, _c_p]),
             "kcache_decode_step": (ctypes.c_int, [_c_p, ctypes.POINTER(_CStepLayer), _c_i32, _c_i32,
                                                   _c_p, _c_p, _c_i32, _c_p]),
@@ -98,6 +101,10 @@ def declared_symbols():
 
 def version():
     return lib().kcache_version().decode()
+
+
+def static_scratch_bytes():
+    return int(lib().kcache_static_scratch_bytes())
 
 
 def workspace_bytes(B, H, S_cap, N):
@@ -256,6 +263,27 @@ class Context:
         self._check(lib().kcache_decode_attention(
             self._h, ctypes.byref(cache.c), _ptr(q), H, _ptr(seq_lens), int(N), _ptr(out),
             _ptr(idx_out), _ptr(w_out), int(gather_mode), _stream_ptr(stream)))
+        return out
+
+    def decode_attention_static(self, cache, q, seq_lens, N, out, idx_out=None, w_out=None,
+                                stream=None):
+        """kcache_decode_attention_static: the caller passes every output; nothing is allocated."""
+        B, H, d = q.shape
+        if (B, d) != (cache.c.B, cache.c.d) or q.dtype != cache.v.dtype or not q.is_contiguous():
+            raise ValueError("q does not match the cache")
+        if seq_lens.dtype != torch.int32 or seq_lens.numel() != B or not seq_lens.is_cuda:
+            raise ValueError("seq_lens must be a device int32 [B] tensor")
+        for t, dt in ((out, torch.float32), (idx_out, torch.int32), (w_out, torch.float32)):
+            if t is not None and (t.dtype != dt or not t.is_contiguous() or not t.is_cuda):
+                raise ValueError("output tensors must be contiguous device tensors of the ABI type")
+        if out is None or out.shape != (B, H, d):
+            raise ValueError("out must be a device fp32 [B][H][d] tensor")
+        for t in (idx_out, w_out):
+            if t is not None and tuple(t.shape) != (B, H, N):
+                raise ValueError("idx_out / w_out must be [B][H][N]")
+        self._check(lib().kcache_decode_attention_static(
+            self._h, ctypes.byref(cache.c), _ptr(q), H, _ptr(seq_lens), int(N), _ptr(out),
+            _ptr(idx_out), _ptr(w_out), _stream_ptr(stream)))
         return out
 
     def full_attention(self, cache, q, seq_lens, out=None, stream=None):

@@ -17,6 +17,17 @@
 #include "../../include/kcache.h"
 #include "kc_internal.h"
 
+// ---- scratch of the entry point that allocates nothing (kcache_decode_attention_static).
+// The array lives in the code object: every GPU the library runs on holds its own copy, at
+// its own address, until the process ends.  In host code the array's name is only a handle
+// for hipGetSymbolAddress, never an address: the device address is looked up once per
+// device (static_scratch_for, called from kcache_create) and passed to the kernels like any
+// other workspace.
+constexpr size_t kStaticWorkBytes = (size_t)48 << 20;  // candidates, partials, positions, weights
+constexpr size_t kStaticTickets = 16384;               // arrival counters, one int per KV unit
+constexpr size_t kStaticScratchBytes = kStaticWorkBytes + kStaticTickets * sizeof(int);
+static __device__ __align__(256) unsigned char kc_static_scratch[kStaticScratchBytes];
+
 namespace {
 
 thread_local std::string g_create_error;
@@ -98,6 +109,32 @@ struct ProfRec {
 constexpr int kMaxParts = 64;
 constexpr int kMaxLanes = 4;
 
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void* g_static_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of the scratch array.  `device` must be current.
+hipError_t static_scratch_for(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> g(g_static_mu);
+  if (!g_static_ptr[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(kc_static_scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_static_ptr[device] = p;
+  }
+  *out = g_static_ptr[device];
+  return hipSuccess;
+}
+
+// Clears n ints.  A kernel, not hipMemsetAsync: memset nodes recorded into a captured graph
+// have replayed wrongly on this platform.
+__global__ __launch_bounds__(256) void zero_ints_kernel(int* p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
 }  // namespace
 
 struct kc_ctx {
@@ -110,6 +147,7 @@ struct kc_ctx {
   void* ws = nullptr;
   size_t ws_bytes = 0;
   int* flags = nullptr;  // [0] device-check bits, [16] probe sink
+  void* static_scratch = nullptr;  // this device's copy of kc_static_scratch
   std::string err;
   int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 1,
       renorm = 0, step_split = 0, gqa_dedup = 0;
@@ -541,6 +579,8 @@ int kcache_create(kc_ctx** out, int device, size_t workspace_bytes_hint) {
       return bail("hipEventCreate", e);
   if ((e = hipMalloc((void**)&c->flags, 256)) != hipSuccess) return bail("hipMalloc", e);
   if ((e = hipMemset(c->flags, 0, 256)) != hipSuccess) return bail("hipMemset", e);
+  if ((e = static_scratch_for(device, &c->static_scratch)) != hipSuccess)
+    return bail("hipGetSymbolAddress(static scratch)", e);
   if (workspace_bytes_hint) {
     int rc = ensure_workspace(c, workspace_bytes_hint);
     if (rc != KC_OK) {
@@ -900,6 +940,51 @@ int kcache_full_attention(kc_ctx* c, const kc_layer_cache* cache, const void* q_
   KC_HIP(c, hipEventRecord(c->ev_last, st));
   c->have_last = true;
   return KC_OK;
+}
+
+size_t kcache_static_scratch_bytes(void) { return kStaticWorkBytes; }
+
+int kcache_decode_attention_static(kc_ctx* c, const kc_layer_cache* cache, const void* q_dev,
+                                   int32_t H, const int32_t* seq_lens_dev, int32_t N,
+                                   float* out_dev, int32_t* idx_out_dev, float* w_out_dev,
+                                   void* stream) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  const char* why;
+  int rc = shape_status(cache, H == 0 ? -1 : H, N, &why);
+  if (rc != KC_OK) return fail(c, rc, "kcache_decode_attention_static: %s", why);
+  if (!cache->k_dev || !cache->v_host || !q_dev || !seq_lens_dev || !out_dev)
+    return fail(c, KC_ERR_INVALID_ARG, "kcache_decode_attention_static: NULL pointer argument");
+  DeviceGuard g(c->device);
+  if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  void* v_map = nullptr;
+  if ((rc = v_pointer(c, cache, &v_map)) != KC_OK) return rc;
+
+  const int split = kc::kv_split_for(H / cache->Hkv);
+  const size_t tickets = (size_t)cache->B * cache->Hkv * split;
+  const FusedPlan pl = plan_fused(c, cache->B, H, cache->Hkv, cache->S_cap, N, cache->k_fp8, cache->d);
+  if (pl.bytes > kStaticWorkBytes || tickets > kStaticTickets)
+    return fail(c, KC_ERR_WORKSPACE, "kcache_decode_attention_static: this shape needs %zu bytes "
+                "of scratch and %zu tickets, the static scratch holds %zu bytes and %zu tickets; "
+                "use kcache_decode_attention", pl.bytes, tickets, kStaticWorkBytes, kStaticTickets);
+
+  hipStream_t st = (hipStream_t)stream;
+  if (c->store_pending) {  // V rows of an earlier store on the side stream
+    KC_HIP(c, hipStreamWaitEvent(st, c->ev_store, 0));
+    c->store_pending = false;
+  }
+  char* base = static_cast<char*>(c->static_scratch);
+  int* counters = reinterpret_cast<int*>(base + kStaticWorkBytes);
+  // the array keeps whatever the last call (or a call that was cut short) left: tickets
+  // must start at zero
+  hipLaunchKernelGGL(zero_ints_kernel, dim3((unsigned)((tickets + 255) / 256)), dim3(256), 0, st,
+                     counters, (int)tickets);
+  KC_HIP(c, hipGetLastError());
+  const int saved_profile = c->profile;
+  c->profile = 0;  // profiling events would be created on demand: nothing is allocated here
+  rc = enqueue_fused(c, cache, v_map, q_dev, H, seq_lens_dev, N, out_dev, idx_out_dev, w_out_dev,
+                     pl, base, counters, st);
+  c->profile = saved_profile;
+  return rc;
 }
 
 }  // extern "C"
