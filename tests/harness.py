@@ -100,6 +100,26 @@ def sample_units(wl, count, seed=0):
     return sorted(units)[:max(count, len(must))]
 
 
+def check_units_parallel(wl, layer, units, N, out_h, idx_h, w_h, tag="", workers=None):
+    """Oracle + acceptance rule for many units, spread over host threads (the unit generator
+    and the C oracle both release the interpreter lock).  Returns the number of units whose
+    index sets were identical; raises the first failure."""
+    import concurrent.futures as cf
+    import os
+    workers = workers or max(1, min(16, len(os.sched_getaffinity(0))))
+
+    def one(u):
+        b, h = u
+        r = oracle_unit(wl, layer, b, h, N)
+        return check_unit(r, N, out_h[b, h], idx_h[b, h], w_h[b, h],
+                          tag="%s %s layer %d unit (%d,%d) N=%d" % (tag, wl.name, layer, b, h, N))
+
+    if workers == 1 or len(units) < 4:
+        return sum(one(u) for u in units)
+    with cf.ThreadPoolExecutor(max_workers=workers) as ex:
+        return sum(ex.map(one, units))
+
+
 def run_and_check(ctx, wl, layer, cache, q, lens_dev, units, N=None, gather_mode=0, tag=""):
     """One kcache_decode_attention call checked against the oracle on `units`."""
     N = wl.N if N is None else N
@@ -112,9 +132,5 @@ def run_and_check(ctx, wl, layer, cache, q, lens_dev, units, N=None, gather_mode
     torch.cuda.synchronize()
     ctx.device_check()
     out_h, idx_h, w_h = out.cpu().numpy(), idx.cpu().numpy(), w.cpu().numpy()
-    identical = 0
-    for (b, h) in units:
-        r = oracle_unit(wl, layer, b, h, N)
-        identical += check_unit(r, N, out_h[b, h], idx_h[b, h], w_h[b, h],
-                                tag="%s %s layer %d unit (%d,%d) N=%d" % (tag, wl.name, layer, b, h, N))
+    identical = check_units_parallel(wl, layer, units, N, out_h, idx_h, w_h, tag=tag)
     return identical, len(units), (out_h, idx_h, w_h)

@@ -90,30 +90,43 @@ def test_config1_pipelined_parts_give_identical_results(kc, ctx, parts):
         assert np.array_equal(a, b)
 
 
-def test_config3_shape_gqa_bf16_two_layers(kc, ctx):
-    # full per-layer shape of config 3 (B 16, 32 query / 8 KV heads, 8192, N 128, bf16)
+def spread_layers(wl):
+    """First, last and two interior layers."""
+    return (0, wl.L // 3, (2 * wl.L) // 3, wl.L - 1)
+
+
+def big_sample(ctx, per_layer):
+    """The full sample on the default (fused) path; the unfused launches, which every other
+    test also covers, check a smaller one."""
+    return per_layer if ctx.fused_default else max(8, per_layer // 8)
+
+
+def test_config3_shape_gqa_bf16_four_layers(kc, ctx):
+    # full per-layer shape of config 3 (B 16, 32 query / 8 KV heads, 8192, N 128, bf16):
+    # 4 x 64 = 256 sampled units over the first, two interior and the last layer
     wl = ki.config(3)
-    for layer in (0, wl.L - 1):
+    for layer in spread_layers(wl):
         cache, q, lens, _, _ = build_layer(ctx, wl, layer)
-        run_and_check(ctx, wl, layer, cache, q, lens, sample_units(wl, 48, seed=layer))
+        run_and_check(ctx, wl, layer, cache, q, lens, sample_units(wl, big_sample(ctx, 64), seed=layer))
         del cache
 
 
-def test_config2_shape_two_layers(kc, ctx):
-    # full per-layer shape of config 2 (B 8, 32 heads, 32768, N 256, fp16)
+def test_config2_shape_four_layers(kc, ctx):
+    # full per-layer shape of config 2 (B 8, 32 heads, 32768, N 256, fp16): 4 x 64 = 256 units
     wl = ki.config(2)
-    for layer in (0, wl.L - 1):
+    for layer in spread_layers(wl):
         cache, q, lens, _, _ = build_layer(ctx, wl, layer, chunk_T=8192)
-        run_and_check(ctx, wl, layer, cache, q, lens, sample_units(wl, 32, seed=layer))
+        run_and_check(ctx, wl, layer, cache, q, lens, sample_units(wl, big_sample(ctx, 64), seed=layer))
         del cache
 
 
-def test_config5_shape_two_layers(kc, ctx):
-    # full per-layer shape of config 5 (B 2, 40 heads, 65536, N 512, fp16)
+def test_config5_shape_four_layers(kc, ctx):
+    # full per-layer shape of config 5 (B 2, 40 heads, 65536, N 512, fp16): 4 x 64 = 256 of
+    # the 4 x 80 units of the first, two interior and the last layer
     wl = ki.config(5)
-    for layer in (0, wl.L - 1):
+    for layer in spread_layers(wl):
         cache, q, lens, _, _ = build_layer(ctx, wl, layer, chunk_T=16384)
-        run_and_check(ctx, wl, layer, cache, q, lens, sample_units(wl, 24, seed=layer))
+        run_and_check(ctx, wl, layer, cache, q, lens, sample_units(wl, big_sample(ctx, 64), seed=layer))
         del cache
 
 
