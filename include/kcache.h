@@ -17,6 +17,11 @@
  *   - calls enqueue work on the caller's HIP stream and do not synchronise with
  *     the host unless stated; the caller owns q / K / V / out memory, the
  *     library owns only its workspace, its side streams and events;
+ *   - the store / attention / step calls never allocate: a context is sized beforehand
+ *     with kcache_reserve (or the hint of kcache_create), and a call whose shape needs
+ *     more fails with KC_ERR_WORKSPACE before anything is enqueued.  Setting
+ *     KC_OPT_AUTO_GROW lets such a call grow the context instead, at the price of one
+ *     device synchronisation each time it does;
  *   - a context is bound to one device and must not be used from two host
  *     threads at once.
  */
@@ -52,7 +57,8 @@ typedef enum {
                               not serve (see the calls)                             */
   KC_ERR_NOT_PINNED = -3,  /* v_host is not device-mapped host memory (or, with
                               v_in_hbm, not device memory)                           */
-  KC_ERR_WORKSPACE = -4,   /* workspace could not be (re)allocated                   */
+  KC_ERR_WORKSPACE = -4,   /* the context is too small for the call (see kcache_reserve),
+                              or its buffers could not be (re)allocated              */
   KC_ERR_HIP = -5,         /* a HIP runtime call failed; see kcache_last_error       */
   KC_ERR_DEVICE_CHECK = -6 /* a kernel found pos / seq_lens outside the cache        */
 } kc_status;
@@ -118,12 +124,15 @@ typedef enum {
                                 the N kept weights by their sum (section 4 remarks that
                                 TopN "regularized" the softmax; the paper does not say
                                 it renormalises)                                      */
-  KC_OPT_STEP_LANES = 5,     /* kcache_decode_step / kcache_step_graph_create: 1 (default)
-                                runs the layers one after another on the caller's
-                                stream; 2..4 spreads the step over that many internal
-                                streams so that the K scan of one launch overlaps the
-                                tail (merge and V pull) of another; see the next option
-                                for what is spread                                     */
+  KC_OPT_STEP_LANES = 5,     /* kcache_decode_step / kcache_step_graph_create: streams a
+                                step is spread over, so that the K scan of one launch
+                                overlaps the tail (merge and V pull) of another.
+                                0 (default): chosen from the shape - two lanes that each
+                                take half of the batch through all layers in order when
+                                the batch has at least two sequences and half of it still
+                                covers the chip (256 workgroups), else one;
+                                1: the layers one after another on the caller's stream;
+                                2..4: that many lanes holding what KC_OPT_STEP_SPLIT says */
   KC_OPT_GQA_DEDUP = 8,      /* 1: with grouped queries the fused launch pulls the union of
                                 the rows that the heads of a group selected, each row
                                 once, instead of every head's rows separately (same
@@ -131,30 +140,70 @@ typedef enum {
                                 group attend to the same positions).  Used when
                                 (H/Hkv)^2 * N <= 2048 and s <= 131072, otherwise the
                                 per-head pull runs.  0 (default): per-head pulls       */
-  KC_OPT_STEP_SPLIT = 7      /* what the lanes of a step hold.  0 (default): whole layers,
-                                dealt round-robin - only meaningful when every layer's q
-                                is known up front, as in a benchmark of the attention
-                                alone (in a model, layer l+1's query depends on layer l's
-                                output).  1: the sequences of the batch, a contiguous
-                                share per lane, each share running through the layers in
-                                order on its own stream - sequences are independent
-                                (section 3.3), so this keeps every data dependency of a
-                                real decode step                                       */
+  KC_OPT_STEP_SPLIT = 7,     /* what an explicit number of lanes holds.  1 (default): the
+                                sequences of the batch, a contiguous share per lane, each
+                                share running through the layers in order on its own
+                                stream - sequences are independent (section 3.3), so this
+                                keeps every data dependency of a real decode step.
+                                0: whole layers, dealt round-robin - only meaningful when
+                                every layer's q is known up front, as in a benchmark of
+                                the attention alone (in a model, layer l+1's query
+                                depends on layer l's output)                           */
+  KC_OPT_AUTO_GROW = 9       /* 0 (default): a call whose shape needs more workspace,
+                                tickets or staging than the context holds fails with
+                                KC_ERR_WORKSPACE (size the context with kcache_reserve);
+                                1: such a call grows the context itself, which
+                                synchronises the device                                */
 } kc_option;
 
+/* Identifiers for kcache_stat. */
+typedef enum {
+  KC_STAT_REALLOCS = 0,        /* (re)allocations of workspace, tickets or staging buffers
+                                  since the context was created (kcache_create's hint and
+                                  kcache_reserve included)                              */
+  KC_STAT_WORKSPACE_BYTES = 1, /* current workspace size                                */
+  KC_STAT_TICKETS = 2,         /* current number of arrival tickets                     */
+  KC_STAT_STEP_LANES = 3       /* value of KC_OPT_STEP_LANES                            */
+} kc_stat;
+
 /* Create a context on `device` (a HIP device ordinal) with a workspace of at
- * least workspace_bytes_hint bytes (0 is fine: the workspace grows on demand,
- * which synchronises the device once).  *out is set only on success. */
+ * least workspace_bytes_hint bytes (0 is fine: kcache_reserve sizes it later).
+ * *out is set only on success. */
 int kcache_create(kc_ctx** out, int device, size_t workspace_bytes_hint);
 
 /* Wait for the context's side streams, free its workspace.  NULL is accepted. */
 int kcache_destroy(kc_ctx* ctx);
 
-/* Upper bound of the device workspace one decode call of this shape needs on any
- * path (the largest is the unfused one: fp32 scores [B][H][S_cap] plus index /
- * weight buffers [B][H][N]); a step with L lanes needs that many times the fused
- * path's share.  A hint for kcache_create; 0 on invalid sizes. */
+/* Upper bound of the device workspace one single-layer decode call of this shape needs
+ * on any path for d = 128 and 16-bit K (the largest is the unfused one: fp32 scores
+ * [B][H][S_cap] plus index / weight buffers [B][H][N]).  A hint for kcache_create; 0 on
+ * invalid sizes.  kcache_reserve is the exact, shape-aware way to size a context. */
 size_t kcache_workspace_bytes(int32_t B, int32_t H, int32_t S_cap, int32_t N);
+
+/*
+ * Sizes the context for every later call of this shape, so that none of them has to
+ * allocate (and therefore synchronise): workspace, arrival tickets, the pinned and
+ * device staging of KC_GATHER_STAGED, and the lane streams of a step.
+ *   shape        B, Hkv, S_cap, d, dtype, v_in_hbm, k_fp8 are read; the pointers are not
+ *   H, N         as for kcache_decode_attention
+ *   gather_mode  the kc_gather_mode the calls will use
+ *   step_layers  0: single-layer calls only; L > 0: also kcache_decode_step /
+ *                kcache_step_graph_create over L layers of this shape
+ * Takes the options in effect (KC_OPT_FUSED, KC_OPT_FUSED_ROWS, KC_OPT_STEP_LANES,
+ * KC_OPT_STEP_SPLIT) into account: set them first.  Only ever grows the context; call it
+ * once per shape that will be used.  May synchronise the device (it is the one place that
+ * does); fails with KC_ERR_WORKSPACE while a step graph holds the buffers that would
+ * have to move.
+ */
+int kcache_reserve(kc_ctx* ctx, const kc_layer_cache* shape, int32_t H, int32_t N,
+                   int32_t gather_mode, int32_t step_layers);
+
+/* Counters of the context, see kc_stat; -1 for an unknown identifier or a NULL context. */
+int64_t kcache_stat(kc_ctx* ctx, int32_t which);
+
+/* Lanes kcache_decode_step would use for L layers of this shape with the options in
+ * effect (see KC_OPT_STEP_LANES); -1 on NULL arguments.  Host only. */
+int32_t kcache_step_lanes_for(kc_ctx* ctx, const kc_layer_cache* shape, int32_t L, int32_t H);
 
 /* Text of the last error recorded in this context ("" if none).  The pointer
  * stays valid until the next failing call on the context.  ctx == NULL returns

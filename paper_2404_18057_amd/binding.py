@@ -14,7 +14,8 @@ GATHER_ZEROCOPY, GATHER_STAGED = 0, 1
 KERNELS = {"kscan": 0, "select": 1, "gather": 2, "store_k": 3, "store_v": 4, "fused": 5,
            "full": 6}
 OPT_PIPELINE_PARTS, OPT_PROFILE, OPT_STAGED_THREADS, OPT_FUSED, OPT_FUSED_ROWS = 0, 1, 2, 3, 4
-OPT_STEP_LANES, OPT_RENORMALIZE, OPT_STEP_SPLIT, OPT_GQA_DEDUP = 5, 6, 7, 8
+OPT_STEP_LANES, OPT_RENORMALIZE, OPT_STEP_SPLIT, OPT_GQA_DEDUP, OPT_AUTO_GROW = 5, 6, 7, 8, 9
+STAT_REALLOCS, STAT_WORKSPACE_BYTES, STAT_TICKETS, STAT_STEP_LANES = 0, 1, 2, 3
 
 _c_i32, _c_i64, _c_p, _c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
 
@@ -62,6 +63,9 @@ def lib():
             "kcache_workspace_bytes": (_c_sz, [_c_i32, _c_i32, _c_i32, _c_i32]),
             "kcache_last_error": (ctypes.c_char_p, [_c_p]),
             "kcache_set_option": (ctypes.c_int, [_c_p, _c_i32, _c_i64]),
+            "kcache_reserve": (ctypes.c_int, [_c_p, cache_p, _c_i32, _c_i32, _c_i32, _c_i32]),
+            "kcache_stat": (_c_i64, [_c_p, _c_i32]),
+            "kcache_step_lanes_for": (_c_i32, [_c_p, cache_p, _c_i32, _c_i32]),
             "kcache_check_shapes": (ctypes.c_int, [cache_p, _c_i32, _c_i32]),
             "kcache_prefill_store": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_p, _c_p, _c_i32, _c_p,
                                                     _c_p]),
@@ -180,13 +184,29 @@ def _ptr(t):
 
 
 class Context:
-    def __init__(self, device=0, workspace_bytes_hint=0):
+    def __init__(self, device=0, workspace_bytes_hint=0, auto_grow=True):
+        """auto_grow=True sets KC_OPT_AUTO_GROW: calls size the context on demand (handy for
+        tests and scripts; each growth synchronises the device).  With auto_grow=False the
+        library's own default applies: size the context with reserve() first."""
         self._h = _c_p()
         rc = lib().kcache_create(ctypes.byref(self._h), int(device), int(workspace_bytes_hint))
         if rc != 0:
             self._h = None
             raise KCacheError(rc, lib().kcache_last_error(None).decode())
         self.device = torch.device("cuda", int(device))
+        if auto_grow:
+            self.set_option(OPT_AUTO_GROW, 1)
+
+    def reserve(self, cache, H, N, gather_mode=GATHER_ZEROCOPY, step_layers=0):
+        """kcache_reserve for the shape of `cache` (a LayerCache; only its shape fields are read)."""
+        self._check(lib().kcache_reserve(self._h, ctypes.byref(cache.c), int(H), int(N),
+                                         int(gather_mode), int(step_layers)))
+
+    def stat(self, which):
+        return int(lib().kcache_stat(self._h, int(which)))
+
+    def step_lanes_for(self, cache, L, H):
+        return int(lib().kcache_step_lanes_for(self._h, ctypes.byref(cache.c), int(L), int(H)))
 
     def close(self):
         if getattr(self, "_h", None):
@@ -309,8 +329,9 @@ class Context:
         self.set_option(OPT_RENORMALIZE, 1 if on else 0)
 
     def set_step_lanes(self, lanes, split_sequences=False):
-        """Streams a step is spread over; split_sequences: each lane takes a share of the
-        batch through all layers (dependency-preserving) instead of whole layers."""
+        """Streams a step is spread over (0 = chosen from the shape, the library's default);
+        split_sequences: each lane takes a share of the batch through all layers
+        (dependency-preserving) instead of whole layers."""
         self.set_option(OPT_STEP_LANES, lanes)
         self.set_option(OPT_STEP_SPLIT, 1 if split_sequences else 0)
 

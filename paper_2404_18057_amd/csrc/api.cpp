@@ -149,8 +149,11 @@ struct kc_ctx {
   int* flags = nullptr;  // [0] device-check bits, [16] probe sink
   void* static_scratch = nullptr;  // this device's copy of kc_static_scratch
   std::string err;
-  int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 1,
-      renorm = 0, step_split = 0, gqa_dedup = 0;
+  int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 0,
+      renorm = 0, step_split = 1, gqa_dedup = 0;
+  int auto_grow = 0;       // 1: a call may (re)allocate its scratch, synchronising the device
+  bool reserving = false;  // inside kcache_create / kcache_reserve: growth is the point
+  int64_t reallocs = 0;    // (re)allocations of workspace, tickets or staging since creation
   int graphs = 0;          // live step graphs: they hold addresses inside ws / counters
   bool capturing = false;  // a step is being captured into a graph: no profiling events
   hipStream_t lane[kMaxLanes] = {};  // streams of kcache_decode_step with more than one lane
@@ -257,12 +260,25 @@ int collect_profile(kc_ctx* c) {
   return KC_OK;
 }
 
+// Growing a buffer frees the old one, which needs the device idle: that is allowed inside
+// kcache_create / kcache_reserve, and inside the hot calls only with KC_OPT_AUTO_GROW.
+int may_grow(kc_ctx* c, const char* what, size_t need, size_t have) {
+  if (c->reserving || c->auto_grow) return KC_OK;
+  return fail(c, KC_ERR_WORKSPACE, "%s: this call needs %zu, the context holds %zu.  Size the "
+              "context first with kcache_reserve (or a workspace hint at kcache_create), or set "
+              "KC_OPT_AUTO_GROW to let calls grow it, which synchronises the device", what, need,
+              have);
+}
+
 int ensure_workspace(kc_ctx* c, size_t bytes) {
   if (bytes <= c->ws_bytes) return KC_OK;
   if (c->graphs > 0)
     return fail(c, KC_ERR_WORKSPACE, "the workspace would have to grow to %zu bytes while %d step "
                 "graph(s) hold addresses inside it: destroy them first, or create the context "
                 "with a larger workspace hint", bytes, c->graphs);
+  int rc = may_grow(c, "workspace bytes", bytes, c->ws_bytes);
+  if (rc != KC_OK) return rc;
+  c->reallocs += 1;
   KC_HIP(c, hipDeviceSynchronize());
   if (c->ws) (void)hipFree(c->ws);
   c->ws = nullptr;
@@ -274,7 +290,7 @@ int ensure_workspace(kc_ctx* c, size_t bytes) {
   return KC_OK;
 }
 
-int ensure_lanes(kc_ctx* c, int lanes) {
+int ensure_lanes(kc_ctx* c, int lanes) {  // stream / event creation does not synchronise
   for (int i = 0; i < lanes; ++i) {
     if (!c->lane[i]) KC_HIP(c, hipStreamCreateWithFlags(&c->lane[i], hipStreamNonBlocking));
     if (!c->ev_lane[i]) KC_HIP(c, hipEventCreateWithFlags(&c->ev_lane[i], hipEventDisableTiming));
@@ -287,6 +303,9 @@ int ensure_counters(kc_ctx* c, size_t n) {
   if (c->graphs > 0)
     return fail(c, KC_ERR_WORKSPACE, "the ticket counters would have to grow while %d step "
                 "graph(s) hold their address: destroy them first", c->graphs);
+  int rc = may_grow(c, "arrival tickets", n, c->counters_n);
+  if (rc != KC_OK) return rc;
+  c->reallocs += 1;
   KC_HIP(c, hipDeviceSynchronize());
   if (c->counters) (void)hipFree(c->counters);
   c->counters = nullptr;
@@ -318,6 +337,9 @@ int ensure_staged(kc_ctx* c, size_t rows) {
     c->pool = new Pool(std::max(0, c->staged_threads - 1));
   }
   if (rows <= c->staged_rows) return KC_OK;
+  int rc = may_grow(c, "staging rows of the staged gather", rows, c->staged_rows);
+  if (rc != KC_OK) return rc;
+  c->reallocs += 1;
   KC_HIP(c, hipDeviceSynchronize());
   if (c->h_idx) (void)hipHostFree(c->h_idx);
   if (c->h_rows) (void)hipHostFree(c->h_rows);
@@ -582,7 +604,9 @@ int kcache_create(kc_ctx** out, int device, size_t workspace_bytes_hint) {
   if ((e = static_scratch_for(device, &c->static_scratch)) != hipSuccess)
     return bail("hipGetSymbolAddress(static scratch)", e);
   if (workspace_bytes_hint) {
+    c->reserving = true;
     int rc = ensure_workspace(c, workspace_bytes_hint);
+    c->reserving = false;
     if (rc != KC_OK) {
       std::string msg = c->err;
       kcache_destroy(c);
@@ -663,9 +687,12 @@ int kcache_set_option(kc_ctx* c, int32_t option, int64_t value) {
       c->renorm = value != 0;
       return KC_OK;
     case KC_OPT_STEP_LANES:
-      if (value < 1 || value > kMaxLanes)
-        return fail(c, KC_ERR_INVALID_ARG, "step lanes must be in [1, %d]", kMaxLanes);
+      if (value < 0 || value > kMaxLanes)
+        return fail(c, KC_ERR_INVALID_ARG, "step lanes must be in [0, %d]", kMaxLanes);
       c->step_lanes = (int)value;
+      return KC_OK;
+    case KC_OPT_AUTO_GROW:
+      c->auto_grow = value != 0;
       return KC_OK;
     case KC_OPT_FUSED_ROWS:
       if (value < 0 || value > kc::kFusedZFloats || value % kc::kFusedThreads != 0)
@@ -996,14 +1023,65 @@ struct kc_step_graph {
 
 namespace {
 
+// How a step is spread over streams.
+struct StepPlan {
+  int lanes = 1;
+  bool split_seq = false;  // lanes hold shares of the batch (true) or whole layers (false)
+};
+
+// Lanes of a step of L layers over caches of this shape.  KC_OPT_STEP_LANES = 0 chooses:
+// two lanes, each with half of the batch through all layers in order (sequences are
+// independent, so every dependency of a real decode step is kept), as long as each lane's
+// launches still cover the chip; otherwise one lane.  An explicit count is capped by what
+// there is to split.
+StepPlan plan_step(const kc_ctx* c, const kc_layer_cache* shape, int32_t L, int32_t H) {
+  StepPlan p;
+  const int B = shape ? std::max(shape->B, 1) : 1;
+  if (c->step_lanes == 0) {
+    p.split_seq = true;
+    if (shape && B >= 2 && H >= 1 && shape->Hkv >= 1 && H % shape->Hkv == 0) {
+      const int64_t chunks = (shape->S_cap + 1023) / 1024;
+      const int64_t wgs_per_lane =
+          (int64_t)(B / 2) * shape->Hkv * kc::kv_split_for(H / shape->Hkv) * chunks;
+      if (wgs_per_lane >= 256) p.lanes = 2;
+    }
+    return p;
+  }
+  p.split_seq = c->step_split != 0;
+  p.lanes = std::min(c->step_lanes, p.split_seq ? B : std::max(L, 1));
+  return p;
+}
+
+// Workspace bytes and arrival tickets one lane of a step needs for a layer of this shape.
+void step_layer_need(const kc_ctx* c, const kc_layer_cache& cache, int32_t H, int32_t N,
+                     const StepPlan& sp, size_t* bytes, size_t* tickets) {
+  // with sequences split over the lanes each launch covers a share of the batch
+  const int nb_max = sp.split_seq ? (cache.B + sp.lanes - 1) / sp.lanes : cache.B;
+  size_t need = 0;
+  for (int nb = std::max(1, nb_max - 1); nb <= nb_max; ++nb)
+    need = std::max(need, cache.v_in_hbm
+                              ? plan_full(c, nb, H, cache.Hkv, cache.S_cap, cache.d).bytes
+                              : plan_fused(c, nb, H, cache.Hkv, cache.S_cap, N, cache.k_fp8,
+                                           cache.d).bytes);
+  *bytes = std::max(*bytes, need);
+  *tickets = std::max(*tickets, (size_t)nb_max * cache.Hkv * kc::kv_split_for(H / cache.Hkv));
+}
+
 // Validates a step and sizes what it needs; fills the device-visible V addresses.
 int prepare_step(kc_ctx* c, const char* who, const kc_step_layer* layers, int32_t L, int32_t H,
-                 const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N, int lanes,
+                 const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N, StepPlan* sp,
                  std::vector<void*>* v_maps, size_t* lane_bytes, size_t* lane_counters) {
   if (!layers || L < 1) return fail(c, KC_ERR_INVALID_ARG, "%s: no layers", who);
   if (!pos_dev || !seq_lens_dev) return fail(c, KC_ERR_INVALID_ARG, "%s: NULL pointer argument", who);
   size_t need = 0, kv_max = 0;
   v_maps->assign(L, nullptr);
+  {
+    const char* why0;
+    int rc0 = shape_status(&layers[0].cache, H == 0 ? -1 : H, N, &why0);
+    if (rc0 != KC_OK) return fail(c, rc0, "%s: layer 0: %s", who, why0);
+  }
+  *sp = plan_step(c, &layers[0].cache, L, H);
+  const int lanes = sp->lanes;
   for (int l = 0; l < L; ++l) {
     const kc_step_layer& y = layers[l];
     const char* why;
@@ -1020,15 +1098,7 @@ int prepare_step(kc_ctx* c, const char* who, const kc_step_layer* layers, int32_
       return fail(c, KC_ERR_UNSUPPORTED, "%s: layer %d: 8-bit K caches are not supported by "
                   "conventional attention", who, l);
     if ((rc = v_pointer(c, &y.cache, &(*v_maps)[l])) != KC_OK) return rc;
-    // with sequences split over the lanes each launch covers a share of the batch
-    const int nb_max = c->step_split ? (y.cache.B + lanes - 1) / lanes : y.cache.B;
-    for (int nb = std::max(1, nb_max - 1); nb <= nb_max; ++nb)
-      need = std::max(need, y.cache.v_in_hbm
-                                ? plan_full(c, nb, H, y.cache.Hkv, y.cache.S_cap, y.cache.d).bytes
-                                : plan_fused(c, nb, H, y.cache.Hkv, y.cache.S_cap, N,
-                                             y.cache.k_fp8, y.cache.d).bytes);
-    kv_max = std::max(kv_max, (size_t)nb_max * y.cache.Hkv *
-                                  kc::kv_split_for(H / y.cache.Hkv));
+    step_layer_need(c, y.cache, H, N, *sp, &need, &kv_max);
   }
   *lane_bytes = round256(need);
   *lane_counters = (kv_max + 63) & ~(size_t)63;
@@ -1042,9 +1112,10 @@ int prepare_step(kc_ctx* c, const char* who, const kc_step_layer* layers, int32_
 // Enqueues the step on `st` (and, with lanes > 1, on the lane streams forked from and
 // joined back into `st`).  Allocates nothing: usable under stream capture.
 int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
-                 const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N, int lanes,
-                 const std::vector<void*>& v_maps, size_t lane_bytes, size_t lane_counters,
-                 hipStream_t st) {
+                 const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N,
+                 const StepPlan& sp, const std::vector<void*>& v_maps, size_t lane_bytes,
+                 size_t lane_counters, hipStream_t st) {
+  const int lanes = sp.lanes;
   if (lanes > 1) {
     KC_HIP(c, hipEventRecord(c->ev_fork, st));
     for (int i = 0; i < lanes; ++i) KC_HIP(c, hipStreamWaitEvent(c->lane[i], c->ev_fork, 0));
@@ -1073,7 +1144,7 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
   };
   for (int l = 0; l < L; ++l) {
     const kc_step_layer& y = layers[l];
-    if (!c->step_split || lanes == 1) {
+    if (!sp.split_seq || lanes == 1) {
       const int rc = enqueue_layer(y, v_maps[l], pos_dev, seq_lens_dev, l % lanes);
       if (rc != KC_OK) return rc;
       continue;
@@ -1112,13 +1183,6 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
   return KC_OK;
 }
 
-// Lanes actually used: no more than there are layers (or, with the batch split, sequences).
-int step_lane_count(const kc_ctx* c, const kc_step_layer* layers, int32_t L) {
-  int most = std::max(L, 1);
-  if (c->step_split && layers && L >= 1) most = std::max(layers[0].cache.B, 1);
-  return std::min(c->step_lanes, most);
-}
-
 int wait_for_earlier_work(kc_ctx* c, hipStream_t st) {
   if (c->have_last) KC_HIP(c, hipStreamWaitEvent(st, c->ev_last, 0));
   if (c->store_pending) {
@@ -1132,6 +1196,63 @@ int wait_for_earlier_work(kc_ctx* c, hipStream_t st) {
 
 extern "C" {
 
+int kcache_reserve(kc_ctx* c, const kc_layer_cache* shape, int32_t H, int32_t N,
+                   int32_t gather_mode, int32_t step_layers) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  const char* why;
+  int rc = shape_status(shape, H == 0 ? -1 : H, N, &why);
+  if (rc != KC_OK) return fail(c, rc, "kcache_reserve: %s", why);
+  if (gather_mode != KC_GATHER_ZEROCOPY && gather_mode != KC_GATHER_STAGED)
+    return fail(c, KC_ERR_INVALID_ARG, "kcache_reserve: unknown gather mode %d", gather_mode);
+  if (step_layers < 0) return fail(c, KC_ERR_INVALID_ARG, "kcache_reserve: step_layers < 0");
+  DeviceGuard g(c->device);
+  if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  const int B = shape->B, Hkv = shape->Hkv, S_cap = shape->S_cap;
+  const size_t units = (size_t)B * H;
+  const bool plain_rows = !shape->k_fp8 && shape->d == kc::kHeadDim;  // what the unfused path serves
+  // single-layer calls: the fused launch, conventional attention for a layer with V in HBM,
+  // and the separate launches when they are selected (KC_OPT_FUSED off, or the staged gather)
+  size_t bytes = plan_fused(c, B, H, Hkv, S_cap, N, shape->k_fp8, shape->d).bytes;
+  if (shape->v_in_hbm && !shape->k_fp8)
+    bytes = std::max(bytes, plan_full(c, B, H, Hkv, S_cap, shape->d).bytes);
+  if (plain_rows && (!c->fused || gather_mode == KC_GATHER_STAGED))
+    bytes = std::max(bytes, unfused_bytes(units, S_cap, N));
+  size_t tickets = (size_t)B * Hkv * kc::kv_split_for(H / Hkv);
+  // a whole step: one workspace and one set of tickets per lane
+  StepPlan sp;
+  if (step_layers > 0) {
+    sp = plan_step(c, shape, step_layers, H);
+    size_t lane_bytes = 0, lane_tickets = 0;
+    step_layer_need(c, *shape, H, N, sp, &lane_bytes, &lane_tickets);
+    bytes = std::max(bytes, round256(lane_bytes) * sp.lanes);
+    tickets = std::max(tickets, ((lane_tickets + 63) & ~(size_t)63) * sp.lanes);
+  }
+  c->reserving = true;
+  rc = ensure_workspace(c, bytes);
+  if (rc == KC_OK) rc = ensure_counters(c, tickets);
+  if (rc == KC_OK && gather_mode == KC_GATHER_STAGED && plain_rows && !shape->v_in_hbm)
+    rc = ensure_staged(c, units * N);
+  if (rc == KC_OK && sp.lanes > 1) rc = ensure_lanes(c, sp.lanes);
+  c->reserving = false;
+  return rc;
+}
+
+int64_t kcache_stat(kc_ctx* c, int32_t which) {
+  if (!c) return -1;
+  switch (which) {
+    case KC_STAT_REALLOCS: return c->reallocs;
+    case KC_STAT_WORKSPACE_BYTES: return (int64_t)c->ws_bytes;
+    case KC_STAT_TICKETS: return (int64_t)c->counters_n;
+    case KC_STAT_STEP_LANES: return c->step_lanes;
+    default: return -1;
+  }
+}
+
+int32_t kcache_step_lanes_for(kc_ctx* c, const kc_layer_cache* shape, int32_t L, int32_t H) {
+  if (!c || !shape) return -1;
+  return plan_step(c, shape, L, H).lanes;
+}
+
 int kcache_decode_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
                        const int32_t* pos_dev, const int32_t* seq_lens_dev, int32_t N,
                        void* stream) {
@@ -1140,13 +1261,13 @@ int kcache_decode_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_
   if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
   std::vector<void*> v_maps;
   size_t lane_bytes = 0, lane_counters = 0;
-  const int lanes = step_lane_count(c, layers, L);
-  int rc = prepare_step(c, "kcache_decode_step", layers, L, H, pos_dev, seq_lens_dev, N, lanes,
+  StepPlan sp;
+  int rc = prepare_step(c, "kcache_decode_step", layers, L, H, pos_dev, seq_lens_dev, N, &sp,
                         &v_maps, &lane_bytes, &lane_counters);
   if (rc != KC_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   if ((rc = wait_for_earlier_work(c, st)) != KC_OK) return rc;
-  if ((rc = enqueue_step(c, layers, L, H, pos_dev, seq_lens_dev, N, lanes, v_maps, lane_bytes,
+  if ((rc = enqueue_step(c, layers, L, H, pos_dev, seq_lens_dev, N, sp, v_maps, lane_bytes,
                          lane_counters, st)) != KC_OK)
     return rc;
   KC_HIP(c, hipEventRecord(c->ev_last, st));
@@ -1163,9 +1284,9 @@ int kcache_step_graph_create(kc_ctx* c, const kc_step_layer* layers, int32_t L, 
   if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
   std::vector<void*> v_maps;
   size_t lane_bytes = 0, lane_counters = 0;
-  const int lanes = step_lane_count(c, layers, L);
+  StepPlan sp;
   int rc = prepare_step(c, "kcache_step_graph_create", layers, L, H, pos_dev, seq_lens_dev, N,
-                        lanes, &v_maps, &lane_bytes, &lane_counters);
+                        &sp, &v_maps, &lane_bytes, &lane_counters);
   if (rc != KC_OK) return rc;
   // everything the context still has in flight is finished first, so that the captured
   // work depends on nothing outside the graph
@@ -1174,7 +1295,7 @@ int kcache_step_graph_create(kc_ctx* c, const kc_step_layer* layers, int32_t L, 
   c->store_pending = false;
   KC_HIP(c, hipStreamBeginCapture(c->side, hipStreamCaptureModeThreadLocal));
   c->capturing = true;
-  rc = enqueue_step(c, layers, L, H, pos_dev, seq_lens_dev, N, lanes, v_maps, lane_bytes,
+  rc = enqueue_step(c, layers, L, H, pos_dev, seq_lens_dev, N, sp, v_maps, lane_bytes,
                     lane_counters, c->side);
   c->capturing = false;
   hipGraph_t graph = nullptr;
