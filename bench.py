@@ -575,57 +575,77 @@ def prefill_leg(ctx, kc, st, dev, reps=3):
     wall = (time.perf_counter() - t) / reps
     k_ms, k_n = ctx.profile_read("store_k")
     v_ms, v_n = ctx.profile_read("store_v")
+    # for scale: a plain device-to-device copy of the same bytes (read + write traffic of the
+    # same size as the K half, no relayout)
+    scratch = torch.empty_like(k_new)
+    d2d = ctx.probe_copy(scratch, k_new, iters=5)
+    del scratch
     out = {"tokens_per_layer": wl.B * T, "bytes_each_of_K_and_V": nbytes,
            "ms_per_layer": wall * 1e3,
+           "plain_device_copy_GBps": d2d,
            "k_to_hbm_GBps": nbytes * k_n / (k_ms * 1e-3) / 1e9 if k_ms else None,
            "v_to_host_GBps": nbytes * v_n / (v_ms * 1e-3) / 1e9 if v_ms else None,
            "note": "K half reads and writes HBM (2 x bytes of traffic); V half is posted PCIe "
                    "writes from the store kernel into the mapped host cache"}
 
-    # ---- together with decode launches of another layer (a second context: its own streams)
+    # ---- together with attention launches of another layer (a second context: its own streams)
     if st.L > 1:
         other = st.caches[-1]
         q, lens = st.qs[-1], st.lens_dev
         o = torch.empty((wl.B, wl.H, wl.d), dtype=torch.float32, device=dev)
+        other_hbm = kc.LayerCache(other.k, other.v.to(dev))
         ctx2 = kc.Context(0, auto_grow=False)
         ctx2.reserve(other, wl.H, wl.N)
+        ctx2.reserve(other_hbm, wl.H, wl.N)
         side = torch.cuda.Stream()
-        # the decode launch alone
-        ctx2.set_profile(True)
-        with torch.cuda.stream(side):
+        store_v_ms = v_ms / max(v_n, 1)
+        legs = {
+            # HBM-heavy work with no host traffic: stands in for the next layer's compute
+            "with_concurrent_hbm_attention": (
+                "full", lambda: ctx2.full_attention(other_hbm, q, lens, out=o, stream=side),
+                "conventional attention of another layer (K and V rows streamed from HBM, no "
+                "host traffic) on a second stream: the stand-in for layer i+1's compute"),
+            # the KCache decode launch also pulls V rows host-to-device while the store pushes
+            # rows device-to-host
+            "with_concurrent_kcache_decode": (
+                "fused", lambda: ctx2.decode_attention(other, q, lens, wl.N, out=o, stream=side),
+                "fused KCache launches of another layer (K scan from HBM + V-row pulls "
+                "host-to-device) on a second stream: what a decode step of other sequences "
+                "would add while a prompt is being stored"),
+        }
+        for name, (kern, launch, what) in legs.items():
+            ctx2.set_profile(True)
             for _ in range(3):
-                ctx2.decode_attention(other, q, lens, wl.N, out=o, stream=side)
+                launch()
             ctx2.profile_reset()
             for _ in range(20):
-                ctx2.decode_attention(other, q, lens, wl.N, out=o, stream=side)
-        ms, n = ctx2.profile_read("fused")
-        alone_us = ms / n * 1e3
-        # both at once: the store first (its V half takes about as long as `n_dec` launches)
-        n_dec = max(8, int(0.8 * (v_ms / max(v_n, 1)) / (alone_us * 1e-3)))
-        ctx.profile_reset()
-        ctx2.profile_reset()
-        ctx.prefill_store(cache, k_new, v_new, pos)
-        with torch.cuda.stream(side):
-            for _ in range(n_dec):
-                ctx2.decode_attention(other, q, lens, wl.N, out=o, stream=side)
-        ctx.synchronize()
-        ctx2.synchronize()
-        torch.cuda.synchronize()
-        k2_ms, k2_n = ctx.profile_read("store_k")
-        v2_ms, v2_n = ctx.profile_read("store_v")
-        d_ms, d_n = ctx2.profile_read("fused")
-        ctx2.set_profile(False)
+                launch()
+            ms, n = ctx2.profile_read(kern)
+            alone_us = ms / n * 1e3
+            # both at once: the store first, then launches for about 80 % of its V half
+            n_att = max(8, int(0.8 * store_v_ms / (alone_us * 1e-3)))
+            ctx.profile_reset()
+            ctx2.profile_reset()
+            ctx.prefill_store(cache, k_new, v_new, pos)
+            for _ in range(n_att):
+                launch()
+            ctx.synchronize()
+            ctx2.synchronize()
+            torch.cuda.synchronize()
+            k2_ms, k2_n = ctx.profile_read("store_k")
+            v2_ms, v2_n = ctx.profile_read("store_v")
+            d_ms, d_n = ctx2.profile_read(kern)
+            ctx2.set_profile(False)
+            out[name] = {
+                "launches": d_n,
+                "attention_us_alone": alone_us, "attention_us_together": d_ms / d_n * 1e3,
+                "v_to_host_GBps_alone": out["v_to_host_GBps"],
+                "v_to_host_GBps_together": nbytes * v2_n / (v2_ms * 1e-3) / 1e9 if v2_ms else None,
+                "k_to_hbm_GBps_together": nbytes * k2_n / (k2_ms * 1e-3) / 1e9 if k2_ms else None,
+                "note": "V half of one layer's store on the library's side stream together with "
+                        + what + "; the K half of the store runs at the start of the same window"}
         ctx2.close()
-        out["with_concurrent_decode"] = {
-            "decode_launches": d_n,
-            "decode_us_alone": alone_us, "decode_us_together": d_ms / d_n * 1e3,
-            "v_to_host_GBps_alone": out["v_to_host_GBps"],
-            "v_to_host_GBps_together": nbytes * v2_n / (v2_ms * 1e-3) / 1e9 if v2_ms else None,
-            "k_to_hbm_GBps_together": nbytes * k2_n / (k2_ms * 1e-3) / 1e9 if k2_ms else None,
-            "note": "V half of one layer's store on the library's side stream while another "
-                    "layer's fused KCache launches (K scan from HBM + V-row pulls host-to-device) "
-                    "run on a second stream; the K half of the store runs at the start of the "
-                    "same window"}
+        del other_hbm
     ctx.set_profile(False)
     return out
 

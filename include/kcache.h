@@ -149,11 +149,17 @@ typedef enum {
                                 every layer's q is known up front, as in a benchmark of
                                 the attention alone (in a model, layer l+1's query
                                 depends on layer l's output)                           */
-  KC_OPT_AUTO_GROW = 9       /* 0 (default): a call whose shape needs more workspace,
+  KC_OPT_AUTO_GROW = 9,      /* 0 (default): a call whose shape needs more workspace,
                                 tickets or staging than the context holds fails with
                                 KC_ERR_WORKSPACE (size the context with kcache_reserve);
                                 1: such a call grows the context itself, which
                                 synchronises the device                                */
+  KC_OPT_XCD_SPREAD = 10     /* for tests.  0 (default): all workgroups that score one
+                                (sequence, KV head) run on one of the eight XCDs, so the
+                                results they hand to the finishing workgroup stay inside
+                                one L2.  1: they are dealt over all XCDs (slower), so
+                                every hand-over crosses XCD boundaries.  Results are bit
+                                for bit the same                                       */
 } kc_option;
 
 /* Identifiers for kcache_stat. */

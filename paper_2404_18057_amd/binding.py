@@ -14,7 +14,7 @@ GATHER_ZEROCOPY, GATHER_STAGED = 0, 1
 KERNELS = {"kscan": 0, "select": 1, "gather": 2, "store_k": 3, "store_v": 4, "fused": 5,
            "full": 6}
 OPT_PIPELINE_PARTS, OPT_PROFILE, OPT_STAGED_THREADS, OPT_FUSED, OPT_FUSED_ROWS = 0, 1, 2, 3, 4
-OPT_STEP_LANES, OPT_RENORMALIZE, OPT_STEP_SPLIT, OPT_GQA_DEDUP, OPT_AUTO_GROW = 5, 6, 7, 8, 9
+OPT_STEP_LANES, OPT_RENORMALIZE, OPT_STEP_SPLIT, OPT_GQA_DEDUP, OPT_AUTO_GROW, OPT_XCD_SPREAD = 5, 6, 7, 8, 9, 10
 STAT_REALLOCS, STAT_WORKSPACE_BYTES, STAT_TICKETS, STAT_STEP_LANES = 0, 1, 2, 3
 
 _c_i32, _c_i64, _c_p, _c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
@@ -324,6 +324,9 @@ class Context:
 
     def set_gqa_dedup(self, on):
         self.set_option(OPT_GQA_DEDUP, 1 if on else 0)
+
+    def set_xcd_spread(self, on):
+        self.set_option(OPT_XCD_SPREAD, 1 if on else 0)
 
     def set_renormalize(self, on):
         self.set_option(OPT_RENORMALIZE, 1 if on else 0)

@@ -151,6 +151,7 @@ struct kc_ctx {
   std::string err;
   int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 0,
       renorm = 0, step_split = 1, gqa_dedup = 0;
+  int xcd_spread = 0;      // test option: chunks of a unit dealt over all XCDs
   int auto_grow = 0;       // 1: a call may (re)allocate its scratch, synchronising the device
   bool reserving = false;  // inside kcache_create / kcache_reserve: growth is the point
   int64_t reallocs = 0;    // (re)allocations of workspace, tickets or staging since creation
@@ -497,6 +498,7 @@ int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, con
   a.k_fp8 = cache->k_fp8;
   a.d = cache->d;
   a.dedup = c->gqa_dedup;
+  a.spread = c->xcd_spread;
   // 1 / sqrt(d_h), times the cache's 2^k_exp for an 8-bit K cache
   a.scale = ldexpf(inv_sqrt_d(cache->d), cache->k_fp8 ? cache->k_exp : 0);
   KernelTimer t(c, KC_KERNEL_FUSED, st);
@@ -542,6 +544,7 @@ int enqueue_full(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, cons
   a.chunks_cap = pl.chunks_cap;
   a.kv_count = cache->B * a.Hkv;
   a.d = cache->d;
+  a.spread = c->xcd_spread;
   a.scale = inv_sqrt_d(cache->d);
   KernelTimer t(c, KC_KERNEL_FULL, st);
   KC_HIP(c, kc::launch_full(a, cache->dtype, st));
@@ -693,6 +696,9 @@ int kcache_set_option(kc_ctx* c, int32_t option, int64_t value) {
       return KC_OK;
     case KC_OPT_AUTO_GROW:
       c->auto_grow = value != 0;
+      return KC_OK;
+    case KC_OPT_XCD_SPREAD:
+      c->xcd_spread = value != 0;
       return KC_OK;
     case KC_OPT_FUSED_ROWS:
       if (value < 0 || value > kc::kFusedZFloats || value % kc::kFusedThreads != 0)

@@ -251,9 +251,15 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   // and pulling workgroups spread evenly over the XCDs.  (With chunks dealt over all
   // XCDs one slightly slower XCD ended up finishing - and therefore merging and
   // pulling - 80 % of all units, which made it slower still.)
+  //
+  // a.spread (KC_OPT_XCD_SPREAD, for tests) deals consecutive chunks of a unit to consecutive
+  // workgroups instead, i.e. over all eight XCDs: slower, same results; it makes every
+  // hand-over below cross XCD boundaries, so the tests can show that correctness does not
+  // rest on the mapping.
   const int xcd = blockIdx.x % kXcds, in_xcd = blockIdx.x / kXcds;
-  const int chunk = in_xcd % a.chunks_cap;
-  const int ku_rel = xcd + kXcds * (in_xcd / a.chunks_cap);
+  const int chunk = a.spread ? (int)(blockIdx.x % a.chunks_cap) : in_xcd % a.chunks_cap;
+  const int ku_rel =
+      a.spread ? (int)(blockIdx.x / a.chunks_cap) : xcd + kXcds * (in_xcd / a.chunks_cap);
   if (ku_rel >= a.kv_count) return;  // padding of the last group of eight units
   const int ku = a.kv0 + ku_rel;
   const int b = ku / a.Hkv, hk = ku - b * a.Hkv;  // a.Hkv counts launch units per sequence

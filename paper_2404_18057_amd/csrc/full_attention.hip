@@ -41,10 +41,11 @@ __global__ __launch_bounds__(AT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int sub = lane % LPR, rg = lane / LPR;
   // all chunks of a KV unit run on one XCD, unit u on XCD u % 8 (workgroups are
-  // dealt to the XCDs round-robin in launch order)
+  // dealt to the XCDs round-robin in launch order); a.spread (a test option) deals the
+  // chunks of a unit over all XCDs instead
   const int xcd = blockIdx.x % kXcds, in_xcd = blockIdx.x / kXcds;
-  const int chunk = in_xcd % a.chunks_cap;
-  const int ku = xcd + kXcds * (in_xcd / a.chunks_cap);
+  const int chunk = a.spread ? (int)(blockIdx.x % a.chunks_cap) : in_xcd % a.chunks_cap;
+  const int ku = a.spread ? (int)(blockIdx.x / a.chunks_cap) : xcd + kXcds * (in_xcd / a.chunks_cap);
   if (ku >= a.kv_count) return;
   const int b = ku / a.Hkv, hk = ku - b * a.Hkv;  // a.Hkv counts launch units per sequence
   const size_t kv_phys = (size_t)b * (a.Hkv / a.kv_split) + hk / a.kv_split;

@@ -91,6 +91,7 @@ struct FusedArgs {
   int k_fp8;       // 1: K rows are E4M3 codes (128 bytes per row); scale carries 2^k_exp
   int d;           // head dimension: 64, 128 or 256
   int dedup;       // 1: a group's heads pull the union of their V rows once
+  int spread;      // 1: deal the chunks of a unit over all XCDs (test option, see fused_kernel)
   float scale;
 };
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N, int k_row_bytes);
@@ -113,6 +114,7 @@ struct FullArgs {
   int kv_count;
   int kv_split;    // launch units per physical KV head (see kv_split_for)
   int d;           // head dimension: 64, 128 or 256
+  int spread;      // 1: deal the chunks of a unit over all XCDs (test option)
   float scale;
 };
 int full_rows_per_block(int kv_units, int G, int S_cap, int row_bytes);
