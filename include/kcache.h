@@ -154,6 +154,18 @@ typedef enum {
                                 KC_ERR_WORKSPACE (size the context with kcache_reserve);
                                 1: such a call grows the context itself, which
                                 synchronises the device                                */
+  KC_OPT_HOST_STORE_BLOCKS = 11, /* workgroups of the V half of a large kcache_prefill_store
+                                (rows leave as posted PCIe writes): 0 (default) = the
+                                library's choice, 2..4096 = that many.  More workgroups
+                                do not make the link faster but do slow down HBM traffic
+                                that runs at the same time                              */
+  KC_OPT_LANE_STAGGER_US = 12, /* a step with more than one lane: lane i starts i / lanes of
+                                this many microseconds late (a bounded wait on the GPU's
+                                constant clock), so that the lanes' launches do not run
+                                in step and the tail of one falls into the scan of
+                                another.  -1 (default): derived from the shape, about 0.3
+                                launch durations for the second of two lanes; 0: lanes
+                                start together                                         */
   KC_OPT_XCD_SPREAD = 10     /* for tests.  0 (default): all workgroups that score one
                                 (sequence, KV head) run on one of the eight XCDs, so the
                                 results they hand to the finishing workgroup stay inside

@@ -128,6 +128,15 @@ hipError_t static_scratch_for(int device, void** out) {
   return hipSuccess;
 }
 
+// Holds a lane back for `ticks` of the constant 100 MHz clock (see enqueue_step).  Bounded
+// twice over: by the clock, and by an iteration cap that ends the loop even if the clock
+// were to stand still.
+__global__ __launch_bounds__(64) void stagger_kernel(long long ticks) {
+  const long long t0 = wall_clock64();
+  for (int i = 0; i < (1 << 20) && (long long)wall_clock64() - t0 < ticks; ++i)
+    __builtin_amdgcn_s_sleep(64);
+}
+
 // Clears n ints.  A kernel, not hipMemsetAsync: memset nodes recorded into a captured graph
 // have replayed wrongly on this platform.
 __global__ __launch_bounds__(256) void zero_ints_kernel(int* p, int n) {
@@ -151,6 +160,9 @@ struct kc_ctx {
   std::string err;
   int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 0,
       renorm = 0, step_split = 1, gqa_dedup = 0;
+  int lane_stagger_us = -1;   // start of lane i is held back by i / lanes of this; 0 = no
+                              // stagger, -1 = derived from the shape (see plan_step)
+  int host_store_blocks = 0;  // workgroups of a V store to host memory; 0 = the kernel's default
   int xcd_spread = 0;      // test option: chunks of a unit dealt over all XCDs
   int auto_grow = 0;       // 1: a call may (re)allocate its scratch, synchronising the device
   bool reserving = false;  // inside kcache_create / kcache_reserve: growth is the point
@@ -697,6 +709,16 @@ int kcache_set_option(kc_ctx* c, int32_t option, int64_t value) {
     case KC_OPT_AUTO_GROW:
       c->auto_grow = value != 0;
       return KC_OK;
+    case KC_OPT_LANE_STAGGER_US:
+      if (value < -1 || value > 100000)
+        return fail(c, KC_ERR_INVALID_ARG, "lane stagger must be -1 or in [0, 100000] microseconds");
+      c->lane_stagger_us = (int)value;
+      return KC_OK;
+    case KC_OPT_HOST_STORE_BLOCKS:
+      if (value < 0 || value > 4096)
+        return fail(c, KC_ERR_INVALID_ARG, "host store workgroups must be in [0, 4096]");
+      c->host_store_blocks = (int)value;
+      return KC_OK;
     case KC_OPT_XCD_SPREAD:
       c->xcd_spread = value != 0;
       return KC_OK;
@@ -761,8 +783,8 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
   KC_HIP(c, hipStreamWaitEvent(c->store_side, c->ev_fork, 0));
   {
     KernelTimer t(c, KC_KERNEL_STORE_V, c->store_side);
-    KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, nullptr, nullptr, pos_dev, T, c->flags, 1,
-                               c->store_side));
+    KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, nullptr, nullptr, pos_dev, T, c->flags,
+                               c->host_store_blocks > 1 ? c->host_store_blocks : 1, c->store_side));
   }
   KC_HIP(c, hipEventRecord(c->ev_store, c->store_side));
   c->store_pending = true;
@@ -1033,7 +1055,26 @@ namespace {
 struct StepPlan {
   int lanes = 1;
   bool split_seq = false;  // lanes hold shares of the batch (true) or whole layers (false)
+  long long stagger_ticks = 0;  // lane i starts i / lanes of this late (100 MHz ticks)
 };
+
+// Lanes that start together stay in step: their launches take equally long, so their tails
+// (when HBM idles) coincide instead of falling into the other lane's scan.  Holding lane i
+// back once by i / lanes of `stagger` keeps them out of step for the whole step.  Measured on
+// MI355X with two lanes, a delay of about 0.3 launch durations is best (config 2: 10.85 ms
+// per step against 11.09 without); a launch that shares HBM with the other lanes streams its
+// K rows at about 6.6 TB/s / lanes.
+long long stagger_ticks_for(const kc_ctx* c, const kc_layer_cache* shape, const StepPlan& p,
+                            int32_t L) {
+  if (p.lanes < 2 || c->lane_stagger_us == 0) return 0;
+  if (c->lane_stagger_us > 0) return (long long)c->lane_stagger_us * 100;
+  if (L < 4) return 0;  // nothing to keep out of step over a launch or two
+  const double rows = (double)(p.split_seq ? (shape->B + p.lanes - 1) / p.lanes : shape->B) *
+                      shape->Hkv * shape->S_cap;
+  const double launch_us = rows * shape->d * (shape->k_fp8 ? 1 : 2) / (6.6e6 / p.lanes);
+  const double us = std::min(0.3 * launch_us * p.lanes, 2000.0);  // lane 1 of 2: 0.3 launches
+  return (long long)(us * 100.0);
+}
 
 // Lanes of a step of L layers over caches of this shape.  KC_OPT_STEP_LANES = 0 chooses:
 // two lanes, each with half of the batch through all layers in order (sequences are
@@ -1051,10 +1092,12 @@ StepPlan plan_step(const kc_ctx* c, const kc_layer_cache* shape, int32_t L, int3
           (int64_t)(B / 2) * shape->Hkv * kc::kv_split_for(H / shape->Hkv) * chunks;
       if (wgs_per_lane >= 256) p.lanes = 2;
     }
+    if (shape) p.stagger_ticks = stagger_ticks_for(c, shape, p, L);
     return p;
   }
   p.split_seq = c->step_split != 0;
   p.lanes = std::min(c->step_lanes, p.split_seq ? B : std::max(L, 1));
+  if (shape) p.stagger_ticks = stagger_ticks_for(c, shape, p, L);
   return p;
 }
 
@@ -1125,6 +1168,13 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
   if (lanes > 1) {
     KC_HIP(c, hipEventRecord(c->ev_fork, st));
     for (int i = 0; i < lanes; ++i) KC_HIP(c, hipStreamWaitEvent(c->lane[i], c->ev_fork, 0));
+    if (sp.stagger_ticks > 0) {  // see stagger_ticks_for
+      for (int i = 1; i < lanes; ++i) {
+        hipLaunchKernelGGL(stagger_kernel, dim3(1), dim3(64), 0, c->lane[i],
+                           sp.stagger_ticks * i / lanes);
+        KC_HIP(c, hipGetLastError());
+      }
+    }
   }
   // one layer (or, with the batch split over the lanes, one share of its sequences)
   auto enqueue_layer = [&](const kc_step_layer& y, const void* v_map, const int32_t* pos,

@@ -108,7 +108,10 @@ __device__ __forceinline__ void score_chunk(const uint16_t* __restrict__ q_group
                                             const uint16_t* __restrict__ K_unit, int S_cap, int s,
                                             int row0, int R, float scale, float* z) {
   typedef RowLayout<D> RL;
-  constexpr int LPR = RL::LPR, RPL = RL::RPL, U = RL::LOADS, ROWS = RL::ROWS;
+  // 32-lane rows with 8 heads: 8 query pieces and their 8 running scores per lane leave room
+  // for 4 loads in flight, not 8 (the build spilled 184 bytes per lane otherwise)
+  constexpr int LPR = RL::LPR, RPL = RL::RPL, U = (LPR == 32 && G >= 8) ? 4 : RL::LOADS;
+  constexpr int ROWS = U * RPL;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane % LPR, rg = lane / LPR;
   uint4 qv[G];

@@ -405,18 +405,23 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
       pl = ld_dev(&a.part[slot0 + tid].y);
       if (try_prune && (tid < chunks_b - 1 || last_rows > kk)) pb = ld_dev(a.bound + slot0 + tid);
     }
-    float zr[G == 1 ? ZR : 1];  // pruned path: all candidates of the unit in registers, i = j * FT + tid
+    // pruned path: all candidates of the unit in registers, i = j * FT + tid, scores and
+    // positions fetched in the same batch (one round trip for everything the merge reads)
+    float zr[G == 1 ? ZR : 1];
+    int32_t pr[G == 1 ? ZR : 1];
     if (G == 1 && try_prune) {
 #pragma unroll
       for (int j = 0; j < ZH; ++j) {
         const int i = j * FT + tid;
         zr[j] = (i < M) ? ld_dev(cz + i) : -INFINITY;
+        pr[j] = (i < M) ? ld_dev(cp + i) : 0;
       }
       if (big) {
 #pragma unroll
         for (int j = ZH; j < ZR; ++j) {
           const int i = j * FT + tid;
           zr[j] = (i < M) ? ld_dev(cz + i) : -INFINITY;
+          pr[j] = (i < M) ? ld_dev(cp + i) : 0;
         }
       }
     } else if (z_in_lds) {
@@ -457,7 +462,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 
     // Pruned path: candidates below the bound cannot be among the N largest (see r_bound).
     // The survivors are compacted into LDS in candidate order (which is position order, so
-    // ties still go to the lower position) together with their candidate index.
+    // ties still go to the lower position) together with their positions.
     int Mp = M;                                  // entries the selection runs over
     int32_t* src_l = reinterpret_cast<int32_t*>(sm.z) + kFusedZFloats / 2;
     bool pruned = false;
@@ -517,7 +522,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
           if (keep) {
             const int dst = seg_base[j * FW + wave] + __popcll(b & lt_mask);
             sm.z[dst] = zr[j];
-            src_l[dst] = j * FT + tid;
+            src_l[dst] = pr[j];
           }
         };
 #pragma unroll
@@ -532,7 +537,10 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 #pragma unroll
           for (int j = 0; j < ZH; ++j) {
             const int i = j * FT + tid;
-            if (i < M) sm.z[i] = zr[j];
+            if (i < M) {
+              sm.z[i] = zr[j];
+              if (pos_in_lds) pos_l[i] = pr[j];
+            }
           }
         }
       }
@@ -545,19 +553,19 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     // global memory: weights and positions are collected in LDS and written out afterwards
     // in whole lines, and candidate positions that are not in LDS beside the scores are
     // fetched then, all kept entries in one round trip.
-    const bool pos_here = pos_in_lds && !try_prune;   // positions were loaded into pos_l
-    const bool pos_later = !pos_here && stage_out;
+    // positions beside the scores in LDS: pos_l (all candidates) or src_l (the survivors)
+    const bool pos_here = pos_in_lds && !pruned;
+    const bool pos_later = !pos_here && !pruned && stage_out;
     float kept = 0.f;  // this thread's share of the kept softmax mass (renormalised variant)
     auto emit = [&](int r, int i, float v) {
       const float w = expf(v - mx) * inv_Z;
       kept += w;
-      const int ci = pruned ? src_l[i] : i;      // index into the unit's candidate arrays
-      if (stage_out) {
+      if (stage_out) {  // an entry without its position at hand keeps its candidate index
         stage_f[r] = w;
-        stage_i[r] = pos_here ? pos_l[i] : ci;
+        stage_i[r] = pruned ? src_l[i] : pos_here ? pos_l[i] : i;
       } else {
         wu[r] = w;
-        iu[r] = pos_here ? pos_l[i] : ld_dev(cp + ci);
+        iu[r] = pruned ? src_l[i] : pos_here ? pos_l[i] : ld_dev(cp + i);
       }
     };
     if (pruned || z_in_lds)

@@ -7,13 +7,23 @@
 // the mapped host cache, so V rows leave the GPU as posted PCIe writes without
 // a staging copy.
 //
-// The V half is link bound (about 57 GB/s).  Posted writes beyond what the link
-// drains back up into the write path they share with HBM traffic: measured on
-// MI355X, a V store of 32 or more workgroups slows a concurrent K store from
-// 2.3 TB/s to 0.5 TB/s and below, while 16 workgroups (256 KiB of writes in
-// flight) leave it untouched and still reach 49 GB/s.  So the host destination
-// gets a small fixed grid that strides over the tiles; that is also what lets the
-// copy hide under the next layer's compute (paper section 3.2, equations (1)-(2)).
+// The V half is link bound (about 57 GB/s).  Its rows leave as posted PCIe writes, and
+// posted writes beyond what the link drains back up into the write path they share with
+// HBM traffic, so the number of workgroups that write to the host decides how much the
+// store disturbs whatever runs beside it.  Measured on MI355X at config 5's layer (1.34 GB
+// of V; conventional attention of another layer, 424 us alone, as the concurrent HBM-bound
+// work; K store of the same call, 2.4 TB/s of rows alone):
+//
+//   workgroups | V alone  | K store beside it | V beside attention | attention beside it
+//        4     | 45 GB/s  |    2.4 TB/s       |      27 GB/s       |     x 1.07
+//        8     | 48 GB/s  |    2.3-2.4 TB/s   |      31 GB/s       |     x 1.21
+//       20     | 54 GB/s  |    0.9-1.0 TB/s   |      37 GB/s       |     x 1.38
+//       64     | 56 GB/s  |    0.2 TB/s       |      51 GB/s       |     x 1.42
+//
+// A layer's device-to-host copy has the whole next layer to hide under (paper section 3.2,
+// equations (1)-(2)), so what counts is that it does not slow that layer down: the host
+// destination gets a small fixed grid of 8 workgroups (128 KiB of writes in flight) that
+// strides over the tiles; KC_OPT_HOST_STORE_BLOCKS changes it.
 //
 // The K half is a device-to-device relayout.  Measured on MI355X at config 5's layer
 // (1.34 GB of rows) it moves 2.2-2.4 TB/s of rows, i.e. 4.4-4.7 TB/s of combined read and
@@ -28,7 +38,7 @@
 namespace kc {
 namespace {
 
-constexpr int kHostStoreBlocks = 20;  // workgroups of a store whose destination is host memory
+constexpr int kHostStoreBlocks = 8;   // workgroups of a store whose destination is host memory
 constexpr int kTokTile = 4;    // tokens per workgroup
 
 // A row of D 16-bit values is LPR = D / 8 lanes x 16 bytes, so the 256 threads form
@@ -109,27 +119,43 @@ __global__ __launch_bounds__(256) void store_kernel(const uint4* __restrict__ sr
     const bool t_ok = t < T;
     const bool p_ok = p >= 0 && p < S_cap;
     if (t_ok && !p_ok && sub == 0 && hi == 0 && ht == 0) atomicOr(flags, kFlagBadPos);
-    uint4 v[4], v2[4];
-    bool ok[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int hk = (int)ht * kHeadTile + i * HPP + hi;
-      ok[i] = t_ok && p_ok && hk < Hkv;
-      const size_t from = (((size_t)b * T + t) * Hkv + hk) * LPR + sub;
-      if (ok[i]) v[i] = src[from];
-      if (ok[i] && src2) v2[i] = src2[from];
+    // all loads of the tile first, then all stores; everything stays in registers
+    uint4 v0, v1, v2, v3, w0, w1, w2, w3;
+    v0 = v1 = v2 = v3 = w0 = w1 = w2 = w3 = make_uint4(0, 0, 0, 0);
+    const int hk0 = (int)ht * kHeadTile + hi;
+    const bool row_ok = t_ok && p_ok;
+    const bool ok0 = row_ok && hk0 < Hkv, ok1 = row_ok && hk0 + HPP < Hkv,
+               ok2 = row_ok && hk0 + 2 * HPP < Hkv, ok3 = row_ok && hk0 + 3 * HPP < Hkv;
+    const size_t from = (((size_t)b * T + t) * Hkv + hk0) * LPR + sub;
+    const size_t fstep = (size_t)HPP * LPR;
+    if (ok0) v0 = src[from];
+    if (ok1) v1 = src[from + fstep];
+    if (ok2) v2 = src[from + 2 * fstep];
+    if (ok3) v3 = src[from + 3 * fstep];
+    if (src2) {
+      if (ok0) w0 = src2[from];
+      if (ok1) w1 = src2[from + fstep];
+      if (ok2) w2 = src2[from + 2 * fstep];
+      if (ok3) w3 = src2[from + 3 * fstep];
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int hk = (int)ht * kHeadTile + i * HPP + hi;
-      const size_t to = (((size_t)b * Hkv + hk) * S_cap + (size_t)p) * LPR + sub;
-      if (ok[i]) {
-        if constexpr (K8 != 0)
-          reinterpret_cast<uint2*>(dst)[to] = quant_row8<K8 - 1>(v[i], k_exp);
-        else
-          dst[to] = v[i];
-      }
-      if (ok[i] && src2) dst2[to] = v2[i];
+    const size_t to = (((size_t)b * Hkv + hk0) * S_cap + (size_t)(row_ok ? p : 0)) * LPR + sub;
+    const size_t tstep = (size_t)HPP * S_cap * LPR;
+    auto put = [&](bool ok, size_t at, const uint4& x) {
+      if (!ok) return;
+      if constexpr (K8 != 0)
+        reinterpret_cast<uint2*>(dst)[at] = quant_row8<K8 - 1>(x, k_exp);
+      else
+        dst[at] = x;
+    };
+    put(ok0, to, v0);
+    put(ok1, to + tstep, v1);
+    put(ok2, to + 2 * tstep, v2);
+    put(ok3, to + 3 * tstep, v3);
+    if (src2) {
+      if (ok0) dst2[to] = w0;
+      if (ok1) dst2[to + tstep] = w1;
+      if (ok2) dst2[to + 2 * tstep] = w2;
+      if (ok3) dst2[to + 3 * tstep] = w3;
     }
   }
 }
@@ -149,7 +175,7 @@ hipError_t launch_store(const Shape& sh, const void* src, void* dst, const void*
   const long long tiles = (long long)sh.B * t_tiles * h_tiles;
   if (tiles > 0xffffffffLL) return hipErrorInvalidValue;
   long long blocks = tiles;
-  const long long cap = dst_is_host ? kHostStoreBlocks : 0x7fffffffLL;
+  const long long cap = dst_is_host ? (dst_is_host > 1 ? dst_is_host : kHostStoreBlocks) : 0x7fffffffLL;
   if (blocks > cap) blocks = cap;
 #define KC_STORE(K8, LPR)                                                                       \
   hipLaunchKernelGGL((store_kernel<K8, LPR>), dim3((unsigned)blocks), dim3(256), 0, st,         \
