@@ -256,10 +256,10 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   // workgroups instead, i.e. over all eight XCDs: slower, same results; it makes every
   // hand-over below cross XCD boundaries, so the tests can show that correctness does not
   // rest on the mapping.
-  const int xcd = blockIdx.x % kXcds, in_xcd = blockIdx.x / kXcds;
-  const int chunk = a.spread ? (int)(blockIdx.x % a.chunks_cap) : in_xcd % a.chunks_cap;
-  const int ku_rel =
-      a.spread ? (int)(blockIdx.x / a.chunks_cap) : xcd + kXcds * (in_xcd / a.chunks_cap);
+  const unsigned in_xcd = a.spread ? blockIdx.x : blockIdx.x / kXcds;
+  const unsigned group = in_xcd / (unsigned)a.chunks_cap;
+  const int chunk = (int)(in_xcd - group * (unsigned)a.chunks_cap);
+  const int ku_rel = a.spread ? (int)group : (int)(blockIdx.x % kXcds + kXcds * group);
   if (ku_rel >= a.kv_count) return;  // padding of the last group of eight units
   const int ku = a.kv0 + ku_rel;
   const int b = ku / a.Hkv, hk = ku - b * a.Hkv;  // a.Hkv counts launch units per sequence
@@ -405,23 +405,18 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
       pl = ld_dev(&a.part[slot0 + tid].y);
       if (try_prune && (tid < chunks_b - 1 || last_rows > kk)) pb = ld_dev(a.bound + slot0 + tid);
     }
-    // pruned path: all candidates of the unit in registers, i = j * FT + tid, scores and
-    // positions fetched in the same batch (one round trip for everything the merge reads)
-    float zr[G == 1 ? ZR : 1];
-    int32_t pr[G == 1 ? ZR : 1];
+    float zr[G == 1 ? ZR : 1];  // pruned path: all candidates of the unit in registers, i = j * FT + tid
     if (G == 1 && try_prune) {
 #pragma unroll
       for (int j = 0; j < ZH; ++j) {
         const int i = j * FT + tid;
         zr[j] = (i < M) ? ld_dev(cz + i) : -INFINITY;
-        pr[j] = (i < M) ? ld_dev(cp + i) : 0;
       }
       if (big) {
 #pragma unroll
         for (int j = ZH; j < ZR; ++j) {
           const int i = j * FT + tid;
           zr[j] = (i < M) ? ld_dev(cz + i) : -INFINITY;
-          pr[j] = (i < M) ? ld_dev(cp + i) : 0;
         }
       }
     } else if (z_in_lds) {
@@ -462,7 +457,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 
     // Pruned path: candidates below the bound cannot be among the N largest (see r_bound).
     // The survivors are compacted into LDS in candidate order (which is position order, so
-    // ties still go to the lower position) together with their positions.
+    // ties still go to the lower position) together with their candidate index.
     int Mp = M;                                  // entries the selection runs over
     int32_t* src_l = reinterpret_cast<int32_t*>(sm.z) + kFusedZFloats / 2;
     bool pruned = false;
@@ -522,7 +517,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
           if (keep) {
             const int dst = seg_base[j * FW + wave] + __popcll(b & lt_mask);
             sm.z[dst] = zr[j];
-            src_l[dst] = pr[j];
+            src_l[dst] = j * FT + tid;
           }
         };
 #pragma unroll
@@ -537,10 +532,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 #pragma unroll
           for (int j = 0; j < ZH; ++j) {
             const int i = j * FT + tid;
-            if (i < M) {
-              sm.z[i] = zr[j];
-              if (pos_in_lds) pos_l[i] = pr[j];
-            }
+            if (i < M) sm.z[i] = zr[j];
           }
         }
       }
@@ -553,19 +545,19 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     // global memory: weights and positions are collected in LDS and written out afterwards
     // in whole lines, and candidate positions that are not in LDS beside the scores are
     // fetched then, all kept entries in one round trip.
-    // positions beside the scores in LDS: pos_l (all candidates) or src_l (the survivors)
-    const bool pos_here = pos_in_lds && !pruned;
-    const bool pos_later = !pos_here && !pruned && stage_out;
+    const bool pos_here = pos_in_lds && !try_prune;   // positions were loaded into pos_l
+    const bool pos_later = !pos_here && stage_out;
     float kept = 0.f;  // this thread's share of the kept softmax mass (renormalised variant)
     auto emit = [&](int r, int i, float v) {
       const float w = expf(v - mx) * inv_Z;
       kept += w;
-      if (stage_out) {  // an entry without its position at hand keeps its candidate index
+      const int ci = pruned ? src_l[i] : i;      // index into the unit's candidate arrays
+      if (stage_out) {
         stage_f[r] = w;
-        stage_i[r] = pruned ? src_l[i] : pos_here ? pos_l[i] : i;
+        stage_i[r] = pos_here ? pos_l[i] : ci;
       } else {
         wu[r] = w;
-        iu[r] = pruned ? src_l[i] : pos_here ? pos_l[i] : ld_dev(cp + i);
+        iu[r] = pos_here ? pos_l[i] : ld_dev(cp + ci);
       }
     };
     if (pruned || z_in_lds)
