@@ -70,3 +70,56 @@ def test_break_even_formula_reproduces_the_papers_a100_example():
     assert round(r) == g["threshold_s_over_N"]
     assert bench.eq4_break_even(g["bandwidth_gpu_GBps"], g["bandwidth_h2d_GBps"],
                                 overlapped=True) == r / 2
+
+
+def read_sweep():
+    """Rows of the tracked config-4 sweep (profiles/config4_sweep.md): measured on the MI355X."""
+    path = os.path.join(os.path.dirname(GOLDEN), "..", "profiles", "config4_sweep.md")
+    rows = []
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) == 8 and cells[1].isdigit():
+            rows.append(dict(frac=float(cells[0]), N=int(cells[1]), us=float(cells[2]),
+                             tps=float(cells[3]), floor=float(cells[6]), bound=cells[7]))
+    return rows
+
+
+def test_launch_floor_model_follows_table_1_and_equation_3():
+    # K term independent of N, V term proportional to N; the floor is the larger of the two
+    # (equation (3) read with overlapped transfers), so it never falls as N grows and grows in
+    # proportion to N once the V rows bind.
+    wl = ki.config(4)
+    lens = wl.seq_lens()
+    floors = [bench.launch_floor_us(wl, lens, N, 8000.0, 57.2) for N in bench.SWEEP_N]
+    assert all(abs(f[1] - floors[0][1]) < 1e-9 for f in floors)            # K time: no N in it
+    assert all(b[0] >= a[0] for a, b in zip(floors, floors[1:]))
+    for (a, N0), (b, N1) in zip(zip(floors, bench.SWEEP_N), zip(floors[1:], bench.SWEEP_N[1:])):
+        assert abs(b[2] / a[2] - N1 / N0) < 1e-9                            # V time: linear in N
+    link_bound = [f for f in floors if f[2] > f[1]]
+    assert len(link_bound) >= 3 and all(f[0] == f[2] for f in link_bound)
+
+
+def test_measured_sweep_shows_the_trend_of_table_4():
+    # Table 4 of the paper: at a fixed shape throughput does not rise with N.  The tracked
+    # measurement must show the same, stay above the floor of the accounting everywhere, and
+    # scale with N where the host link binds.
+    rows = read_sweep()
+    assert len(rows) == len(bench.SWEEP_N) * len(bench.SWEEP_FRAC)
+    wl = ki.config(4)
+    lens = wl.seq_lens()
+    for frac in bench.SWEEP_FRAC:
+        cells = sorted((r for r in rows if r["frac"] == frac), key=lambda r: r["N"])
+        assert [c["N"] for c in cells] == list(bench.SWEEP_N)
+        for a, b in zip(cells, cells[1:]):
+            # flat (within 5 %) while the K scan binds, falling once the V rows do
+            assert b["tps"] <= a["tps"] * 1.05, "throughput rises with N at fraction %g" % frac
+        for c in cells:
+            floor, t_hbm, t_link = bench.launch_floor_us(wl, lens, c["N"], 8000.0, 57.2)
+            assert abs(floor - c["floor"]) / floor < 0.01          # the table's own floor column
+            assert c["us"] >= floor                                  # nothing beats the floor
+            assert c["bound"] == ("hbm" if t_hbm >= t_link else "host_link")
+            if t_link > 1.5 * t_hbm:                                 # clearly link bound
+                assert c["us"] <= 1.15 * floor
+        by_n = {c["N"]: c["us"] for c in cells}
+        assert abs(by_n[512] / by_n[256] - 2.0) < 0.2               # proportional to N
+        assert cells[-1]["tps"] < 0.25 * cells[0]["tps"]
