@@ -671,7 +671,8 @@ def sweep_leg(ctx, kc, a, pool, dev, probes, first=None, reps=10):
         for N in SWEEP_N:
             ctx.reserve(cache, wl.H, N)
             out = torch.empty((wl.B, wl.H, wl.d), dtype=torch.float32, device=dev)
-            ctx.decode_attention(cache, q, lens_dev, N, out=out)     # warm-up
+            for _ in range(10):      # warm-up (the first launches over a new cache run slower)
+                ctx.decode_attention(cache, q, lens_dev, N, out=out)
             ctx.set_profile(True)
             ctx.profile_reset()
             for _ in range(reps):

@@ -453,10 +453,15 @@ float inv_sqrt_d(int d) { return d == 64 ? 0.125f : d == 256 ? 0.0625f : 0.08838
 // Sizes that a fused KCache launch of this shape needs.
 struct FusedPlan {
   int R, chunks_cap, kk;
+  size_t plan_items;  // ints of the launch plan (dense numbering of the chunks that exist), or 0
   size_t bytes;
 };
-FusedPlan plan_fused(const kc_ctx* c, int B, int H, int Hkv, int S_cap, int N, int k_fp8,
-                     int d = kc::kHeadDim) {
+// in_step: the launch is one of a whole step, where the launch plan is built once per lane
+// and step; a single-layer call builds it every time (4-5 us), so it only takes one for
+// batches of kPlanBatch sequences and more, where lengths that differ are to be expected.
+constexpr int kPlanBatch = 32;
+FusedPlan plan_fused(const kc_ctx* c, int B, int H, int Hkv, int S_cap, int N, int k_fp8, int d,
+                     bool in_step = false) {
   const int split = kc::kv_split_for(H / Hkv), G = H / Hkv / split;  // per launch unit
   FusedPlan p;
   p.R = (c->fused_rows > 0 && c->fused_rows * G <= kc::kFusedZFloats)
@@ -465,15 +470,23 @@ FusedPlan plan_fused(const kc_ctx* c, int B, int H, int Hkv, int S_cap, int N, i
                                        k_fp8 ? d : 2 * d);
   p.chunks_cap = (S_cap + p.R - 1) / p.R;
   p.kk = std::min(N, p.R);
-  p.bytes = fused_bytes((size_t)B * H, p.chunks_cap, p.kk, N);
+  p.plan_items = (c->xcd_spread || (!in_step && B < kPlanBatch))
+                     ? 0
+                     : kc::fused_plan_items(B, Hkv * split, p.chunks_cap);
+  p.bytes = fused_bytes((size_t)B * H, p.chunks_cap, p.kk, N) +
+            round256(p.plan_items * sizeof(int));
   return p;
 }
 
 // One fused KCache launch on `st` with its scratch carved out of `ws` and its tickets in
 // `counters` (both exclusively this launch's until it has finished).
+// `new_plan`: the launch plan in `ws` (if this shape takes one) is (re)built from the lengths
+// first; false only when an earlier launch on `st` has built it in the same `ws` from the same
+// lengths for the same shape (the layers of a step).
 int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, const void* q_dev,
                   int H, const int32_t* seq_lens_dev, int N, float* out_dev, int32_t* idx_out_dev,
-                  float* w_out_dev, const FusedPlan& pl, void* ws, int* counters, hipStream_t st) {
+                  float* w_out_dev, const FusedPlan& pl, void* ws, int* counters, hipStream_t st,
+                  bool new_plan = true) {
   const int B = cache->B, Hkv = cache->Hkv, S_cap = cache->S_cap;
   const size_t units = (size_t)B * H;
   char* p = static_cast<char*>(ws);
@@ -494,6 +507,8 @@ int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, con
   a.idx = idx_out_dev ? idx_out_dev : reinterpret_cast<int32_t*>(p);
   p += round256(units * N * sizeof(int32_t));
   a.w = w_out_dev ? w_out_dev : reinterpret_cast<float*>(p);
+  p += round256(units * N * sizeof(int32_t));
+  a.plan = pl.plan_items ? reinterpret_cast<const int*>(p) : nullptr;
   a.counters = counters;
   a.flags = c->flags;
   a.kv_split = kc::kv_split_for(H / Hkv);
@@ -513,7 +528,10 @@ int enqueue_fused(kc_ctx* c, const kc_layer_cache* cache, const void* v_map, con
   a.spread = c->xcd_spread;
   // 1 / sqrt(d_h), times the cache's 2^k_exp for an 8-bit K cache
   a.scale = ldexpf(inv_sqrt_d(cache->d), cache->k_fp8 ? cache->k_exp : 0);
-  KernelTimer t(c, KC_KERNEL_FUSED, st);
+  KernelTimer t(c, KC_KERNEL_FUSED, st);  // the plan, when one is built, is part of the launch's cost
+  if (a.plan && new_plan)
+    KC_HIP(c, kc::launch_fused_plan(seq_lens_dev, B, a.Hkv, S_cap, pl.R, const_cast<int*>(a.plan),
+                                    st));
   KC_HIP(c, kc::launch_fused(a, cache->dtype, a.kv_count, st));
   return KC_OK;
 }
@@ -1111,7 +1129,7 @@ void step_layer_need(const kc_ctx* c, const kc_layer_cache& cache, int32_t H, in
     need = std::max(need, cache.v_in_hbm
                               ? plan_full(c, nb, H, cache.Hkv, cache.S_cap, cache.d).bytes
                               : plan_fused(c, nb, H, cache.Hkv, cache.S_cap, N, cache.k_fp8,
-                                           cache.d).bytes);
+                                           cache.d, true).bytes);
   *bytes = std::max(*bytes, need);
   *tickets = std::max(*tickets, (size_t)nb_max * cache.Hkv * kc::kv_split_for(H / cache.Hkv));
 }
@@ -1176,6 +1194,17 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
       }
     }
   }
+  // The launch plan of a lane's workspace (see enqueue_fused) stays valid from layer to layer
+  // as long as the shape and the lengths it was built from are the same and nothing else
+  // has used the workspace in between.
+  struct PlanKey {
+    int B = 0, units = 0, S_cap = 0, R = 0;
+    const int32_t* lens = nullptr;
+    bool operator==(const PlanKey& o) const {
+      return B == o.B && units == o.units && S_cap == o.S_cap && R == o.R && lens == o.lens;
+    }
+  };
+  PlanKey lane_plan[kMaxLanes];
   // one layer (or, with the batch split over the lanes, one share of its sequences)
   auto enqueue_layer = [&](const kc_step_layer& y, const void* v_map, const int32_t* pos,
                            const int32_t* lens, int ln) -> int {
@@ -1191,12 +1220,21 @@ int enqueue_step(kc_ctx* c, const kc_step_layer* layers, int32_t L, int32_t H,
     }
     if (y.cache.v_in_hbm) {
       const FullPlan pl = plan_full(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, y.cache.d);
+      lane_plan[ln] = PlanKey();  // conventional attention uses the same workspace
       return enqueue_full(c, &y.cache, v_map, y.q_dev, H, lens, y.out_dev, pl, ws, counters, s);
     }
     const FusedPlan pl =
-        plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N, y.cache.k_fp8, y.cache.d);
+        plan_fused(c, y.cache.B, H, y.cache.Hkv, y.cache.S_cap, N, y.cache.k_fp8, y.cache.d, true);
+    PlanKey key;
+    key.B = y.cache.B;
+    key.units = y.cache.Hkv * kc::kv_split_for(H / y.cache.Hkv);
+    key.S_cap = y.cache.S_cap;
+    key.R = pl.R;
+    key.lens = lens;
+    const bool new_plan = !(key == lane_plan[ln]);
+    lane_plan[ln] = key;
     return enqueue_fused(c, &y.cache, v_map, y.q_dev, H, lens, N, y.out_dev, y.idx_out_dev,
-                         y.w_out_dev, pl, ws, counters, s);
+                         y.w_out_dev, pl, ws, counters, s, new_plan);
   };
   for (int l = 0; l < L; ++l) {
     const kc_step_layer& y = layers[l];

@@ -43,6 +43,8 @@ constexpr int FT = kFusedThreads;
 constexpr int FW = FT / 64;
 
 constexpr int kStage = 1024;  // entries of each of the two staging arrays inside hist[]
+constexpr int kPlanSeqs = 2048;    // longest batch a launch plan is built for
+constexpr int kPlanChunkBits = 12; // a plan entry is (unit of the XCD) << 12 | chunk
 constexpr int kPruneCands = 2 * kFusedZFloats;  // candidates of a unit the pruned merge can take
 
 template <int D>
@@ -256,11 +258,31 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   // workgroups instead, i.e. over all eight XCDs: slower, same results; it makes every
   // hand-over below cross XCD boundaries, so the tests can show that correctness does not
   // rest on the mapping.
-  const unsigned in_xcd = a.spread ? blockIdx.x : blockIdx.x / kXcds;
-  const unsigned group = in_xcd / (unsigned)a.chunks_cap;
-  const int chunk = (int)(in_xcd - group * (unsigned)a.chunks_cap);
-  const int ku_rel = a.spread ? (int)group : (int)(blockIdx.x % kXcds + kXcds * group);
-  if (ku_rel >= a.kv_count) return;  // padding of the last group of eight units
+  //
+  // a.plan (batches that may be ragged).  The grid has a workgroup for every chunk of every
+  // sequence's capacity, because the lengths live in device memory; a workgroup whose chunk
+  // lies beyond its sequence's length exits at once, but it still takes a slot for the time of
+  // a launch, in between the working ones (config 4: 47 % of the grid, 7 % of the launch).
+  // plan_kernel therefore numbers the chunks that exist densely, in the same order: entry i
+  // of the plan names the unit and chunk of the i-th workgroup of every XCD, plan[0] counts
+  // them, and the workgroups left over come last in the grid and exit while the last units
+  // finish.  For full-length sequences the numbering is the one above.
+  int chunk, ku_rel;
+  if (a.plan) {
+    const unsigned i = blockIdx.x / kXcds;
+    if (i >= (unsigned)a.plan[0]) return;
+    const unsigned e = (unsigned)a.plan[1 + i];
+    const unsigned per = (unsigned)a.Hkv / kXcds, uix = e >> kPlanChunkBits;
+    const unsigned bq = uix / per;
+    chunk = (int)(e & ((1u << kPlanChunkBits) - 1u));
+    ku_rel = (int)(bq * (unsigned)a.Hkv + blockIdx.x % kXcds + kXcds * (uix - bq * per));
+  } else {
+    const unsigned in_xcd = a.spread ? blockIdx.x : blockIdx.x / kXcds;
+    const unsigned group = in_xcd / (unsigned)a.chunks_cap;
+    chunk = (int)(in_xcd - group * (unsigned)a.chunks_cap);
+    ku_rel = a.spread ? (int)group : (int)(blockIdx.x % kXcds + kXcds * group);
+    if (ku_rel >= a.kv_count) return;  // padding of the last group of eight units
+  }
   const int ku = a.kv0 + ku_rel;
   const int b = ku / a.Hkv, hk = ku - b * a.Hkv;  // a.Hkv counts launch units per sequence
   const size_t kv_phys = (size_t)b * (a.Hkv / a.kv_split) + hk / a.kv_split;
@@ -614,6 +636,56 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   }
 }
 
+// Fills the plan of a launch (see fused_kernel): one workgroup walks the lengths, builds the
+// running count of chunks per sequence and writes one entry per chunk that exists, in the
+// order an XCD's workgroups take them: sequence by sequence, within a sequence unit by unit
+// (the units of that sequence on the XCD), within a unit chunk by chunk.  An entry packs
+// (sequence * units-per-XCD + unit) << 12 | chunk; it is the same for all eight XCDs.
+__global__ __launch_bounds__(FT) void plan_kernel(const int32_t* __restrict__ seq_lens, int B,
+                                                  int per, int S_cap, int R,
+                                                  int* __restrict__ plan) {
+  __shared__ int pre[kPlanSeqs + 1];   // chunks (times units per XCD) before sequence b
+  __shared__ int cnt[kPlanSeqs];       // chunks of sequence b
+  __shared__ int wave_tot[FW];
+  __shared__ int tile_total;
+  const int tid = threadIdx.x;
+  int carry = 0;
+  for (int b0 = 0; b0 < B; b0 += FT) {
+    const int b = b0 + tid;
+    int c = 0;
+    if (b < B) {
+      int s = seq_lens[b];
+      s = s < 1 ? 0 : (s > S_cap ? S_cap : s);
+      c = (s + R - 1) / R;
+      c = c < 1 ? 1 : c;  // an empty sequence keeps one chunk: it writes the defined empty result
+      cnt[b] = c;
+    }
+    const int items = c * per;
+    const int ex = block_excl_scan<FT>(items, wave_tot);
+    if (b < B) pre[b] = carry + ex;
+    if (tid == FT - 1) tile_total = ex + items;
+    __syncthreads();
+    carry += tile_total;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    pre[B] = carry;
+    plan[0] = carry;
+  }
+  __syncthreads();
+  const int total = pre[B];
+  for (int e = tid; e < total; e += FT) {
+    int lo = 0, hi = B;  // largest b with pre[b] <= e
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (pre[mid] <= e) lo = mid; else hi = mid;
+    }
+    const int rem = e - pre[lo], c = cnt[lo];
+    const int jj = rem / c;
+    plan[1 + e] = ((lo * per + jj) << kPlanChunkBits) | (rem - jj * c);
+  }
+}
+
 template <int DT, bool K8, int D>
 hipError_t launch_dt(const FusedArgs& a, int G, int kv_count, hipStream_t st) {
   // eight XCDs each get ceil(kv_count / 8) units' worth of blocks
@@ -663,6 +735,26 @@ int fused_rows_per_block(int kv_units, int G, int S_cap, int N, int k_row_bytes)
   while (R > kFusedThreads && (int64_t)kv_units * ((S_cap + R - 1) / R) < 512 && fits(R / 2))
     R /= 2;
   return R;
+}
+
+size_t fused_plan_items(int B, int units_per_seq, int chunks_cap) {
+  if (B < 1 || B > kPlanSeqs || units_per_seq % kXcds != 0 || chunks_cap < 2 ||
+      chunks_cap > (1 << kPlanChunkBits))
+    return 0;
+  const long long per_xcd = (long long)B * (units_per_seq / kXcds);
+  if (per_xcd >= (1ll << (31 - kPlanChunkBits))) return 0;
+  // a launch of fewer than four rounds of workgroups has nothing to gain
+  if (per_xcd * chunks_cap * kXcds < 2048) return 0;
+  return (size_t)(per_xcd * chunks_cap) + 1;
+}
+
+hipError_t launch_fused_plan(const int32_t* seq_lens, int B, int units_per_seq, int S_cap, int R,
+                             int* plan, hipStream_t st) {
+  if (B < 1 || B > kPlanSeqs || units_per_seq % kXcds != 0 || R < 1 || !plan)
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(FT), 0, st, seq_lens, B, units_per_seq / kXcds,
+                     S_cap, R, plan);
+  return hipGetLastError();
 }
 
 hipError_t launch_fused(const FusedArgs& a, int dtype, int kv_count, hipStream_t st) {

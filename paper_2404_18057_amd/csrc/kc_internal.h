@@ -92,10 +92,21 @@ struct FusedArgs {
   int d;           // head dimension: 64, 128 or 256
   int dedup;       // 1: a group's heads pull the union of their V rows once
   int spread;      // 1: deal the chunks of a unit over all XCDs (test option, see fused_kernel)
+  const int* plan; // dense numbering of the chunks that exist (launch_fused_plan), or null
   float scale;
 };
 int fused_rows_per_block(int kv_units, int G, int S_cap, int N, int k_row_bytes);
 hipError_t launch_fused(const FusedArgs& a, int dtype, int kv_count, hipStream_t st);
+
+// Dense numbering of the chunks that exist, for batches whose sequences are shorter than the
+// cache's capacity (see fused_kernel).  fused_plan_items: ints the plan of such a launch
+// occupies, or 0 when the launch shape does not take one (units per sequence not a multiple
+// of eight, a single chunk of capacity, a small grid, sizes beyond the packing).
+// launch_fused_plan fills it from the lengths in device memory; it must run before the fused
+// launch that reads it, on the same stream, whenever the lengths may have changed.
+size_t fused_plan_items(int B, int units_per_seq, int chunks_cap);
+hipError_t launch_fused_plan(const int32_t* seq_lens, int B, int units_per_seq, int S_cap, int R,
+                             int* plan, hipStream_t st);
 
 // Conventional attention with K and V in HBM (full_attention.hip).
 struct FullArgs {

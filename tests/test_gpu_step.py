@@ -7,6 +7,7 @@ import torch
 
 import kcache_inputs as ki
 from harness import build_layer, oracle_unit, check_unit, sample_units
+import oracle
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -279,3 +280,50 @@ def test_graph_launch_at_the_benchmark_shape_matches_the_oracle(kc):
         graph.close()
     finally:
         c.close()
+
+
+@pytest.mark.parametrize("lanes", [0, 1])
+def test_ragged_step_graph_follows_changing_lengths(kc, ctx, lanes):
+    """A ragged batch large enough for the launch plan (the dense numbering of the chunks that
+    exist is rebuilt from the lengths at the start of every step): the captured step is replayed
+    after the lengths in device memory have changed - some sequences shrink to one chunk, one
+    grows to the full capacity - and every replay is checked against the oracle."""
+    wl = ki.config(4, B=40, H=16, Hkv=16, S_cap=8192, N=48, len_range=(600, 8192))
+    L = 2
+    layers, lens, gen = make_model(kc, ctx, wl, L)
+    lens_h0 = lens.cpu().numpy().copy()
+    for y, (k, v) in zip(layers, gen):          # the whole capacity holds generated rows
+        y["cache"].k.copy_(k)
+        y["cache"].v.copy_(v)
+        y["k_new"], y["v_new"] = None, None     # nothing is appended: lengths move freely
+    pos = (lens - 1).to(torch.int32)
+    ctx.set_step_lanes(lanes, split_sequences=True)
+    graph = ctx.step_graph(layers, wl.H, pos, lens, wl.N)
+    ctx.set_step_lanes(0, split_sequences=True)
+    rng = np.random.default_rng(9)
+    try:
+        for rep in range(3):
+            new = lens_h0.copy()
+            if rep > 0:
+                new = rng.integers(1, wl.S_cap + 1, size=wl.B).astype(np.int32)
+                new[0], new[1], new[-1] = wl.S_cap, 1, 513
+            lens.copy_(torch.from_numpy(new))
+            clear(layers)
+            graph.launch()
+            ctx.synchronize()
+            torch.cuda.synchronize()
+            ctx.device_check()
+            for l, y in enumerate(layers):
+                out, idx, w = (y["out"].cpu().numpy(), y["idx_out"].cpu().numpy(),
+                               y["w_out"].cpu().numpy())
+                kb, vb = ki.as_bits(gen[l][0]), ki.as_bits(gen[l][1])
+                qb = ki.as_bits(y["q"])
+                for (b, h) in [(0, 0), (1, 3), (wl.B - 1, wl.H - 1), (7, 2), (20, 15), (33, 9)]:
+                    s = int(new[b])
+                    r = oracle.decode_unit(qb[b, h], kb[b, h, :s], vb[b, h, :s], oracle.F16, wl.N,
+                                           want_scores=True)
+                    r["v"] = oracle.decode16(vb[b, h, :s], oracle.F16)
+                    check_unit(r, wl.N, out[b, h], idx[b, h], w[b, h],
+                               tag="replay %d layer %d (%d,%d) s=%d" % (rep, l, b, h, s))
+    finally:
+        graph.close()
