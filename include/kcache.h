@@ -122,7 +122,7 @@ typedef enum {
   KC_OPT_RENORMALIZE = 6,    /* 0 (default): the kept weights are the full-context softmax
                                 values, as Table 1 writes them; 1: variant that divides
                                 the N kept weights by their sum (section 4 remarks that
-                                TopN "regularized" the softmax; the paper does not say
+                                TopN acts as a regulariser of the softmax; the paper does not say
                                 it renormalises)                                      */
   KC_OPT_STEP_LANES = 5,     /* kcache_decode_step / kcache_step_graph_create: streams a
                                 step is spread over, so that the K scan of one launch

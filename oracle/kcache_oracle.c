@@ -256,8 +256,8 @@ int kcache_oracle_unit(const uint16_t* q, const uint16_t* K, const uint16_t* V, 
 /*
  * Variant of the unit above in which the N kept weights are divided by their sum,
  * so that they add up to one.  The paper's formula does not do this (Table 1:
- * TopN applied to the softmax output); its remark in section 4 that TopN
- * "regularized the softmax" is the only hint at such a variant.  Everything up
+ * TopN applied to the softmax output); its passing remark in section 4 that TopN
+ * acts as a regulariser of the softmax is the only hint at such a variant.  Everything up
  * to and including the selection is identical.
  */
 int kcache_oracle_unit_renormalised(const uint16_t* q, const uint16_t* K, const uint16_t* V,

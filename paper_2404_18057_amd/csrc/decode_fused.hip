@@ -117,7 +117,7 @@ __device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp
 // De-duplicated V pull for a group of G query heads (grouped-query attention): the heads
 // of a group read the same V head, so a position that several of them selected is pulled
 // over the host link once and accumulated into each head's output with that head's weight.
-// (The paper says only that the method "applies to ... GQA", section 5; every head still
+// (The paper only states that the method carries over to GQA, section 5; every head still
 // makes its own selection.)  The union is built with a bitmap over the positions:
 //   bm[w]          bit p % 32 of word p / 32 set iff some head kept position p
 //   pf[w]          number of set bits before word w: the rank of a kept position in the

@@ -1,8 +1,8 @@
 // Conventional decode attention with the K and the V cache both in HBM:
 // out = softmax(q K^T / sqrt(d_h)) V over all cached positions (paper section 2;
 // Table 1 rows S and A of plain MHA).  It serves the layers whose V cache the
-// method leaves in HBM (section 3.1 and the caption of Table 2: "the first L
-// layers") and it is the baseline of the break-even analysis (section 3.2,
+// method leaves in HBM (section 3.1 and the caption of Table 2: the leading L
+// layers) and it is the baseline of the break-even analysis (section 3.2,
 // equations (3)-(4)): per position it reads a K row and a V row, 512 bytes,
 // where the KCache path reads 256 bytes from HBM and N rows over the host link.
 //
