@@ -67,3 +67,41 @@ def test_create_without_a_gpu_reports_an_error_instead_of_crashing():
     with pytest.raises(kc.KCacheError) as e:
         kc.Context(0)
     assert e.value.status == -5 and "HIP" in str(e.value)
+
+
+def test_header_is_plain_c_and_a_c_caller_links(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 with nothing but the standard
+    headers, and a C program that names every entry point links against the library and can
+    call the calls that need no GPU."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc = os.path.join(root, "include")
+    names = kc.declared_symbols()
+    src = tmp_path / "caller.c"
+    refs = "\n".join("  p[%d] = (fn)%s;" % (i, n) for i, n in enumerate(names))
+    src.write_text("""
+#include <stdio.h>
+#include "kcache.h"
+typedef void (*fn)(void);
+int main(void) {
+  fn p[%d];
+  kc_layer_cache c = {0};
+%s
+  c.B = 8; c.Hkv = 32; c.S_cap = 32768; c.d = 128; c.dtype = KC_F16;
+  if (kcache_check_shapes(&c, 32, 256) != KC_OK) return 2;
+  c.d = 96;
+  if (kcache_check_shapes(&c, 32, 256) != KC_ERR_UNSUPPORTED) return 3;
+  if (kcache_workspace_bytes(8, 32, 32768, 256) == 0) return 4;
+  if (kcache_static_scratch_bytes() != ((size_t)48 << 20)) return 5;
+  printf("%%s %%d\\n", kcache_version(), p[0] != 0);
+  return 0;
+}
+""" % (len(names), refs))
+    exe = tmp_path / "caller"
+    libdir = os.path.dirname(kc.lib_path())
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", inc, str(src),
+                           "-o", str(exe), "-L", libdir, "-l:libkcache.so",
+                           "-Wl,-rpath," + libdir])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert out.stdout.startswith("kcache-gfx950")
