@@ -549,47 +549,30 @@ def main():
 
 
 def prefill_leg(ctx, kc, st, dev, reps=3):
-    """Store of one layer's full context through kcache_prefill_store (Figure 1, upper half:
-    K rows to the HBM cache, V rows device-to-host), timed
+    """Store of one layer's full context (Figure 1, upper half: K rows to the HBM cache, V rows
+    device-to-host) in both forms the library offers - kcache_prefill_store (positions in device
+    memory, V half by a kernel that writes into the mapped host cache) and
+    kcache_prefill_store_at (positions on the host, V half by the copy engine) - each timed
       alone      as a whole (wall clock, K and V halves overlapped) and per half (HIP events);
-      together   with KCache decode launches of another layer running on a second context
-                 and stream while the V half is in flight: section 3.2, equations (1)-(2),
-                 asks that layer i's device-to-host copy hides under layer i+1's work, so
-                 neither may slow the other down.
+      together   with attention launches of another layer running on a second context and
+                 stream while the V half is in flight: section 3.2, equations (1)-(2), asks
+                 that layer i's device-to-host copy hides under layer i+1's work, so neither
+                 may slow the other down.
     The rows written are the ones already in the cache, so its contents do not change."""
     wl, cache = st.wl, st.caches[0]
     T = wl.S_cap
     k_new = cache.k.permute(0, 2, 1, 3).contiguous()
     v_new = cache.v.to(dev).permute(0, 2, 1, 3).contiguous()
     pos = torch.zeros(wl.B, dtype=torch.int32, device=dev)
+    pos_host = [0] * wl.B
     nbytes = k_new.numel() * k_new.element_size()
-    ctx.prefill_store(cache, k_new, v_new, pos)          # warm-up
-    ctx.synchronize()
-    torch.cuda.synchronize()
-    ctx.set_profile(True)
-    ctx.profile_reset()
-    t = time.perf_counter()
-    for _ in range(reps):
-        ctx.prefill_store(cache, k_new, v_new, pos)
-    ctx.synchronize()
-    torch.cuda.synchronize()
-    wall = (time.perf_counter() - t) / reps
-    k_ms, k_n = ctx.profile_read("store_k")
-    v_ms, v_n = ctx.profile_read("store_v")
     # for scale: a plain device-to-device copy of the same bytes (read + write traffic of the
     # same size as the K half, no relayout)
     scratch = torch.empty_like(k_new)
     d2d = ctx.probe_copy(scratch, k_new, iters=5)
     del scratch
     out = {"tokens_per_layer": wl.B * T, "bytes_each_of_K_and_V": nbytes,
-           "ms_per_layer": wall * 1e3,
-           "plain_device_copy_GBps": d2d,
-           "k_to_hbm_GBps": nbytes * k_n / (k_ms * 1e-3) / 1e9 if k_ms else None,
-           "v_to_host_GBps": nbytes * v_n / (v_ms * 1e-3) / 1e9 if v_ms else None,
-           "note": "K half reads and writes HBM (2 x bytes of traffic); V half is posted PCIe "
-                   "writes from the store kernel into the mapped host cache"}
-
-    # ---- together with attention launches of another layer (a second context: its own streams)
+           "plain_device_copy_GBps": d2d}
     if st.L > 1:
         other = st.caches[-1]
         q, lens = st.qs[-1], st.lens_dev
@@ -599,7 +582,6 @@ def prefill_leg(ctx, kc, st, dev, reps=3):
         ctx2.reserve(other, wl.H, wl.N)
         ctx2.reserve(other_hbm, wl.H, wl.N)
         side = torch.cuda.Stream()
-        store_v_ms = v_ms / max(v_n, 1)
         legs = {
             # HBM-heavy work with no host traffic: stands in for the next layer's compute
             "with_concurrent_hbm_attention": (
@@ -614,6 +596,28 @@ def prefill_leg(ctx, kc, st, dev, reps=3):
                 "host-to-device) on a second stream: what a decode step of other sequences "
                 "would add while a prompt is being stored"),
         }
+    else:
+        legs = {}
+    forms = {"kernel_store": lambda: ctx.prefill_store(cache, k_new, v_new, pos),
+             "copy_engine_store": lambda: ctx.prefill_store_at(cache, k_new, v_new, pos_host)}
+    for form, store in forms.items():
+        store()                                              # warm-up
+        ctx.synchronize()
+        torch.cuda.synchronize()
+        ctx.set_profile(True)
+        ctx.profile_reset()
+        t = time.perf_counter()
+        for _ in range(reps):
+            store()
+            ctx.synchronize()                                # one store at a time
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t) / reps
+        k_ms, k_n = ctx.profile_read("store_k")
+        v_ms, v_n = ctx.profile_read("store_v")
+        ent = {"ms_per_layer": wall * 1e3,
+               "k_to_hbm_GBps": nbytes * k_n / (k_ms * 1e-3) / 1e9 if k_ms else None,
+               "v_to_host_GBps": nbytes * v_n / (v_ms * 1e-3) / 1e9 if v_ms else None}
+        store_v_ms = v_ms / max(v_n, 1)
         for name, (kern, launch, what) in legs.items():
             ctx2.set_profile(True)
             for _ in range(3):
@@ -627,7 +631,7 @@ def prefill_leg(ctx, kc, st, dev, reps=3):
             n_att = max(8, int(0.8 * store_v_ms / (alone_us * 1e-3)))
             ctx.profile_reset()
             ctx2.profile_reset()
-            ctx.prefill_store(cache, k_new, v_new, pos)
+            store()
             for _ in range(n_att):
                 launch()
             ctx.synchronize()
@@ -637,17 +641,20 @@ def prefill_leg(ctx, kc, st, dev, reps=3):
             v2_ms, v2_n = ctx.profile_read("store_v")
             d_ms, d_n = ctx2.profile_read(kern)
             ctx2.set_profile(False)
-            out[name] = {
+            ent[name] = {
                 "launches": d_n,
                 "attention_us_alone": alone_us, "attention_us_together": d_ms / d_n * 1e3,
-                "v_to_host_GBps_alone": out["v_to_host_GBps"],
                 "v_to_host_GBps_together": nbytes * v2_n / (v2_ms * 1e-3) / 1e9 if v2_ms else None,
                 "k_to_hbm_GBps_together": nbytes * k2_n / (k2_ms * 1e-3) / 1e9 if k2_ms else None,
-                "note": "V half of one layer's store on the library's side stream together with "
-                        + what + "; the K half of the store runs at the start of the same window"}
+                "what": "V half of one layer's store together with " + what}
+        ctx.set_profile(False)
+        out[form] = ent
+    if legs:
         ctx2.close()
-        del other_hbm
-    ctx.set_profile(False)
+    out["note"] = ("K half reads and writes HBM (2 x bytes of traffic).  kernel_store: V half as "
+                   "posted PCIe writes from a store kernel into the mapped host cache; "
+                   "copy_engine_store: V half as one strided device-to-host copy per (sequence, "
+                   "KV head) issued to the copy engine")
     return out
 
 

@@ -258,6 +258,24 @@ int kcache_prefill_store(kc_ctx* ctx, const kc_layer_cache* cache, const void* k
                          void* done_event);
 
 /*
+ * The same store for a caller that holds the positions on the host, as a serving loop does
+ * for a prompt it is about to prefill (Figure 1 upper half; section 3.2, equations (1)-(2):
+ * the V states of a layer are copied to CPU memory asynchronously, hidden under the next
+ * layer's compute).  Knowing the positions on the host lets the V half go through the GPU's
+ * copy engine (one strided device-to-host copy per (sequence, KV head)) instead of a kernel:
+ * measured on MI355X it neither takes compute units nor slows HBM-bound work that runs beside
+ * it, and keeps its own rate while such work runs.
+ *   pos_host   host int32 [B], read during the call; [pos, pos + T) must fit the capacity
+ *              (KC_ERR_INVALID_ARG otherwise, nothing is enqueued); at most 1024 sequences
+ *   others     as for kcache_prefill_store
+ * Small stores (decode appends) and layers with v_in_hbm take the same kernel path as
+ * kcache_prefill_store.  Not meant for stream capture (the copies are issued by the host).
+ */
+int kcache_prefill_store_at(kc_ctx* ctx, const kc_layer_cache* cache, const void* k_new_dev,
+                            const void* v_new_dev, const int32_t* pos_host, int32_t T,
+                            void* stream, void* done_event);
+
+/*
  * KCache attention for one layer and one decode step (section 3.1; Table 1 rows
  * S~ = TopN(softmax(Q K^T / sqrt(d_h))) and A~ = S~ Part(V); section 3.3 for
  * the per-(sequence, head) granularity).

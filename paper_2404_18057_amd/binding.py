@@ -69,6 +69,8 @@ def lib():
             "kcache_check_shapes": (ctypes.c_int, [cache_p, _c_i32, _c_i32]),
             "kcache_prefill_store": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_p, _c_p, _c_i32, _c_p,
                                                     _c_p]),
+            "kcache_prefill_store_at": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_p, _c_p, _c_i32, _c_p,
+                                                       _c_p]),
             "kcache_decode_attention": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_i32, _c_p, _c_i32,
                                                        _c_p, _c_p, _c_p, _c_i32, _c_p]),
             "kcache_decode_attention_static": (ctypes.c_int, [_c_p, cache_p, _c_p, _c_i32, _c_p,
@@ -261,6 +263,24 @@ class Context:
             ev = ctypes.c_void_p(done_event.cuda_event)
         self._check(lib().kcache_prefill_store(self._h, ctypes.byref(cache.c), _ptr(k_new),
                                                _ptr(v_new), _ptr(pos), T, _stream_ptr(stream), ev))
+
+    def prefill_store_at(self, cache, k_new, v_new, pos_host, stream=None, done_event=None):
+        """kcache_prefill_store_at: pos_host is a host int32 sequence / array of B positions."""
+        B, T, Hkv, d = k_new.shape
+        if v_new.shape != k_new.shape or (B, Hkv, d) != (cache.c.B, cache.c.Hkv, cache.c.d):
+            raise ValueError("k_new / v_new shape does not match the cache")
+        if k_new.dtype != cache.v.dtype or v_new.dtype != cache.v.dtype:
+            raise ValueError("k_new / v_new dtype does not match the cache")
+        if not (k_new.is_contiguous() and v_new.is_contiguous()):
+            raise ValueError("inputs must be contiguous")
+        pos = (ctypes.c_int32 * B)(*[int(p) for p in pos_host])
+        ev = None
+        if done_event is not None:
+            if not done_event.cuda_event:
+                done_event.record(torch.cuda.current_stream() if stream is None else stream)
+            ev = ctypes.c_void_p(done_event.cuda_event)
+        self._check(lib().kcache_prefill_store_at(self._h, ctypes.byref(cache.c), _ptr(k_new),
+                                                  _ptr(v_new), pos, T, _stream_ptr(stream), ev))
 
     def decode_attention(self, cache, q, seq_lens, N, out=None, idx_out=None, w_out=None,
                          gather_mode=GATHER_ZEROCOPY, stream=None):

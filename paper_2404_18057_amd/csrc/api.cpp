@@ -108,6 +108,8 @@ struct ProfRec {
 
 constexpr int kMaxParts = 64;
 constexpr int kMaxLanes = 4;
+constexpr int kPosSlots = 8;     // stores with host-side positions that may be in flight at once
+constexpr int kPosInts = 1024;   // sequences per such store
 
 constexpr int kMaxDevices = 64;
 std::mutex g_static_mu;
@@ -137,6 +139,16 @@ __global__ __launch_bounds__(64) void stagger_kernel(long long ticks) {
     __builtin_amdgcn_s_sleep(64);
 }
 
+// Writes up to 64 ints, handed over by value, to device memory: positions that the caller
+// holds on the host reach the store kernel without a staging buffer whose reuse would have to
+// be guarded.
+struct IntPack {
+  int32_t v[64];
+};
+__global__ __launch_bounds__(64) void set_ints_kernel(int32_t* dst, IntPack vals, int n) {
+  if ((int)threadIdx.x < n) dst[threadIdx.x] = vals.v[threadIdx.x];
+}
+
 // Clears n ints.  A kernel, not hipMemsetAsync: memset nodes recorded into a captured graph
 // have replayed wrongly on this platform.
 __global__ __launch_bounds__(256) void zero_ints_kernel(int* p, int n) {
@@ -157,6 +169,8 @@ struct kc_ctx {
   size_t ws_bytes = 0;
   int* flags = nullptr;  // [0] device-check bits, [16] probe sink
   void* static_scratch = nullptr;  // this device's copy of kc_static_scratch
+  int32_t* d_pos = nullptr;        // kPosSlots x kPosInts: positions of kcache_prefill_store_at
+  int pos_slot = 0;
   std::string err;
   int parts = 0, profile = 0, staged_threads = 8, fused = 1, fused_rows = 0, step_lanes = 0,
       renorm = 0, step_split = 1, gqa_dedup = 0;
@@ -636,6 +650,8 @@ int kcache_create(kc_ctx** out, int device, size_t workspace_bytes_hint) {
   if ((e = hipMemset(c->flags, 0, 256)) != hipSuccess) return bail("hipMemset", e);
   if ((e = static_scratch_for(device, &c->static_scratch)) != hipSuccess)
     return bail("hipGetSymbolAddress(static scratch)", e);
+  if ((e = hipMalloc((void**)&c->d_pos, kPosSlots * kPosInts * sizeof(int32_t))) != hipSuccess)
+    return bail("hipMalloc", e);
   if (workspace_bytes_hint) {
     c->reserving = true;
     int rc = ensure_workspace(c, workspace_bytes_hint);
@@ -684,6 +700,7 @@ int kcache_destroy(kc_ctx* c) {
   if (c->store_side) (void)hipStreamDestroy(c->store_side);
   if (c->ws) (void)hipFree(c->ws);
   if (c->flags) (void)hipFree(c->flags);
+  if (c->d_pos) (void)hipFree(c->d_pos);
   if (c->counters) (void)hipFree(c->counters);
   if (c->h_idx) (void)hipHostFree(c->h_idx);
   if (c->h_rows) (void)hipHostFree(c->h_rows);
@@ -803,6 +820,81 @@ int kcache_prefill_store(kc_ctx* c, const kc_layer_cache* cache, const void* k_n
     KernelTimer t(c, KC_KERNEL_STORE_V, c->store_side);
     KC_HIP(c, kc::launch_store(sh, v_new_dev, v_map, nullptr, nullptr, pos_dev, T, c->flags,
                                c->host_store_blocks > 1 ? c->host_store_blocks : 1, c->store_side));
+  }
+  KC_HIP(c, hipEventRecord(c->ev_store, c->store_side));
+  c->store_pending = true;
+  if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, c->store_side));
+  {
+    KernelTimer t(c, KC_KERNEL_STORE_K, st);
+    KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, nullptr, nullptr, pos_dev, T,
+                               c->flags, 0, st, cache->k_fp8, cache->k_exp));
+  }
+  return KC_OK;
+}
+
+int kcache_prefill_store_at(kc_ctx* c, const kc_layer_cache* cache, const void* k_new_dev,
+                            const void* v_new_dev, const int32_t* pos_host, int32_t T,
+                            void* stream, void* done_event) {
+  if (!c) return KC_ERR_INVALID_ARG;
+  const char* why;
+  int rc = shape_status(cache, 0, 0, &why);
+  if (rc != KC_OK) return fail(c, rc, "kcache_prefill_store_at: %s", why);
+  if (!cache->k_dev || !cache->v_host || !k_new_dev || !v_new_dev || !pos_host)
+    return fail(c, KC_ERR_INVALID_ARG, "kcache_prefill_store_at: NULL pointer argument");
+  if (T < 1 || T > cache->S_cap)
+    return fail(c, KC_ERR_INVALID_ARG, "kcache_prefill_store_at: T = %d outside [1, S_cap = %d]",
+                T, cache->S_cap);
+  const int B = cache->B, Hkv = cache->Hkv;
+  if (B > kPosInts)
+    return fail(c, KC_ERR_UNSUPPORTED, "kcache_prefill_store_at: at most %d sequences per call",
+                kPosInts);
+  for (int b = 0; b < B; ++b)
+    if (pos_host[b] < 0 || (int64_t)pos_host[b] + T > cache->S_cap)
+      return fail(c, KC_ERR_INVALID_ARG, "kcache_prefill_store_at: sequence %d: rows [%d, %d) do "
+                  "not fit the capacity %d", b, pos_host[b], pos_host[b] + T, cache->S_cap);
+  DeviceGuard g(c->device);
+  if (!g.ok) return fail(c, KC_ERR_HIP, "hipSetDevice(%d) failed", c->device);
+  void* v_map = nullptr;
+  if ((rc = v_pointer(c, cache, &v_map)) != KC_OK) return rc;
+
+  hipStream_t st = (hipStream_t)stream;
+  // the positions, for the kernel that stores K (and V, where a kernel stores it)
+  int32_t* pos_dev = c->d_pos + (size_t)c->pos_slot * kPosInts;
+  c->pos_slot = (c->pos_slot + 1) % kPosSlots;
+  for (int b0 = 0; b0 < B; b0 += 64) {
+    IntPack pack;
+    const int n = std::min(64, B - b0);
+    for (int i = 0; i < 64; ++i) pack.v[i] = i < n ? pos_host[b0 + i] : 0;
+    hipLaunchKernelGGL(set_ints_kernel, dim3(1), dim3(64), 0, st, pos_dev + b0, pack, n);
+    KC_HIP(c, hipGetLastError());
+  }
+  const kc::Shape sh{B, 0, Hkv, cache->S_cap, 0, cache->dtype, 0, cache->d};
+  const bool small = (int64_t)B * T * Hkv <= 4096;
+  if (cache->v_in_hbm || small) {  // as kcache_prefill_store: one launch for both halves
+    {
+      KernelTimer t(c, KC_KERNEL_STORE_K, st);
+      KC_HIP(c, kc::launch_store(sh, k_new_dev, cache->k_dev, v_new_dev, v_map, pos_dev, T,
+                                 c->flags, cache->v_in_hbm ? 0 : 1, st, cache->k_fp8,
+                                 cache->k_exp));
+    }
+    if (done_event) KC_HIP(c, hipEventRecord((hipEvent_t)done_event, st));
+    return KC_OK;
+  }
+  // V half: the copy engine moves the rows of every (sequence, KV head), T rows of one head
+  // out of the token-major source (pitch Hkv rows) into a dense run of the host cache
+  KC_HIP(c, hipEventRecord(c->ev_fork, st));
+  KC_HIP(c, hipStreamWaitEvent(c->store_side, c->ev_fork, 0));
+  {
+    KernelTimer t(c, KC_KERNEL_STORE_V, c->store_side);
+    const size_t row = (size_t)cache->d * 2;
+    for (int b = 0; b < B; ++b)
+      for (int hk = 0; hk < Hkv; ++hk) {
+        char* dst = static_cast<char*>(cache->v_host) +
+                    (((size_t)b * Hkv + hk) * cache->S_cap + (size_t)pos_host[b]) * row;
+        const char* src = static_cast<const char*>(v_new_dev) + ((size_t)b * T * Hkv + hk) * row;
+        KC_HIP(c, hipMemcpy2DAsync(dst, row, src, (size_t)Hkv * row, row, (size_t)T,
+                                   hipMemcpyDeviceToHost, c->store_side));
+      }
   }
   KC_HIP(c, hipEventRecord(c->ev_store, c->store_side));
   c->store_pending = true;

@@ -253,12 +253,18 @@ def test_fused_counters_are_clean_between_calls_of_different_shapes(kc, ctx):
 
 
 # ------------------------------------------------------------------ cache store
-def test_prefill_store_matches_oracle_bit_for_bit(kc, ctx):
+@pytest.mark.parametrize("T,S_cap,pos,host_pos", [
+    (37, 100, [0, 63, 11], False),       # a small store: one launch for both halves
+    (37, 100, [0, 63, 11], True),
+    (600, 700, [0, 100, 37], False),     # a large one: V half on the side stream, by the kernel
+    (600, 700, [0, 100, 37], True),      # ... and by the copy engine (positions on the host)
+])
+def test_prefill_store_matches_oracle_bit_for_bit(kc, ctx, T, S_cap, pos, host_pos):
     rng = np.random.default_rng(5)
-    B, T, Hkv, d, S_cap = 3, 37, 5, 128, 100
+    B, Hkv, d = 3, 5, 128
     k_new = bits_t(rng.standard_normal((B, T, Hkv, d)))
     v_new = bits_t(rng.standard_normal((B, T, Hkv, d)))
-    pos = np.array([0, 63, 11], np.int32)
+    pos = np.array(pos, np.int32)
     k_cache = torch.full((B, Hkv, S_cap, d), 9.0, dtype=torch.float16)
     v_cache = torch.full((B, Hkv, S_cap, d), -9.0, dtype=torch.float16)
     k_ref, v_ref = ki.as_bits(k_cache).copy(), ki.as_bits(v_cache).copy()
@@ -268,8 +274,11 @@ def test_prefill_store_matches_oracle_bit_for_bit(kc, ctx):
     v_host.copy_(v_cache)
     cache = kc.LayerCache(k_dev, v_host)
     done = torch.cuda.Event()
-    ctx.prefill_store(cache, k_new.to(DEV), v_new.to(DEV), torch.from_numpy(pos).to(DEV),
-                      done_event=done)
+    if host_pos:
+        ctx.prefill_store_at(cache, k_new.to(DEV), v_new.to(DEV), pos, done_event=done)
+    else:
+        ctx.prefill_store(cache, k_new.to(DEV), v_new.to(DEV), torch.from_numpy(pos).to(DEV),
+                          done_event=done)
     done.synchronize()
     assert np.array_equal(ki.as_bits(v_host), v_ref)
     torch.cuda.synchronize()
@@ -344,6 +353,11 @@ def test_bad_arguments_are_reported_not_fatal(kc, ctx):
     with pytest.raises(kc.KCacheError) as e:
         ctx.device_check()
     assert e.value.status == -6
+    # with the positions on the host the same mistake is refused before anything is enqueued
+    with pytest.raises(kc.KCacheError) as e:
+        ctx.prefill_store_at(cache, k_new, k_new, [wl.S_cap - 2])
+    assert e.value.status == -1
+    ctx.device_check()
 
 
 def test_non_finite_scores_never_leave_the_sequence(kc, ctx):
