@@ -114,6 +114,53 @@ __device__ __forceinline__ void pull_and_accumulate(const uint4* __restrict__ Vp
   __syncthreads();
 }
 
+// The same for one unit by ONE wavefront (no barrier): RPL row slots, 8 row reads per slot
+// in flight.  il / wl: the unit's positions and weights in LDS.
+template <int DT, int D>
+__device__ __forceinline__ void wave_pull(const uint4* __restrict__ Vp, const int32_t* il,
+                                          const float* wl, int n_eff, int s, int* flags,
+                                          float* __restrict__ out_u) {
+  constexpr int LPR = RowLayout<D>::LPR, RPL = RowLayout<D>::RPL;
+  const int lane = threadIdx.x & 63;
+  const int sub = lane % LPR, rg = lane / LPR;
+  constexpr int UNR = 8;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int j0 = rg; j0 < n_eff; j0 += RPL * UNR) {
+    int t[UNR];
+    float w[UNR];
+    uint4 v[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int j = j0 + u * RPL;
+      t[u] = (j < n_eff) ? il[j] : -1;
+      w[u] = (j < n_eff) ? wl[j] : 0.f;
+      if (t[u] >= s) {  // the selection only emits positions below s
+        atomicOr(flags, kFlagBadIndex);
+        t[u] = -1;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      v[u] = make_uint4(0, 0, 0, 0);
+      if (t[u] >= 0) v[u] = Vp[(size_t)t[u] * LPR + sub];
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+      if (t[u] >= 0) fma8<DT>(acc, v[u], w[u]);
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) acc[i] += __shfl_xor(acc[i], m, 64);
+  }
+  if (rg == 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out_u[sub * 8 + i] = acc[i];
+  }
+}
+
 // De-duplicated V pull for a group of G query heads (grouped-query attention): the heads
 // of a group read the same V head, so a position that several of them selected is pulled
 // over the host link once and accumulated into each head's output with that head's weight.
@@ -305,6 +352,8 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     }
     return;
   }
+  // grouped queries: 512 words per wavefront for the selections the wavefronts run on their own
+  __shared__ uint32_t whist[G > 1 ? FW * 512 : 1];
   const int row0 = chunk * R;
   if (row0 >= s) return;
   const int chunks_b = (s + R - 1) / R;
@@ -337,6 +386,35 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   const int last_rows_b = s - (chunks_b - 1) * R;
   const int n_full = kk < R ? chunks_b - (last_rows_b > kk ? 0 : 1) : 0;
   const int r_bound = (G == 1 && n_full > 0 && n > kk) ? (N + n_full - 1) / n_full : 0;
+  if constexpr (G > 1) {
+    // Grouped queries: the G heads are independent, so each wavefront takes a head and does
+    // its statistics and its selection alone, without a workgroup barrier, all heads at the
+    // same time (head after head with the whole workgroup, the selection costs G times a
+    // barrier-bound 8 us per chunk and outweighs the K scan it follows).
+    const int wave = tid >> 6, lane = tid & 63;
+#pragma unroll 1
+    for (int g = wave; g < G; g += FW) {
+      const float* zg = sm.z + g * R;
+      const size_t slot = (size_t)(unit0 + g) * a.chunks_cap + chunk;
+      auto key = [&](int i) { return zg[i]; };
+      float m, z_lo, l;
+      bool finite;
+      wave_minmax(key, n, z_lo, m, finite);
+      float* cz = a.cand_z + slot * kk;
+      int32_t* cp = a.cand_pos + slot * kk;
+      wave_topn<true>(key, n, k_loc, z_lo, m, finite, whist + wave * 512,
+                      [&](int r, int i, float v) {
+                        st_dev(cz + r, v);
+                        st_dev(cp + r, row0 + i);
+                      }, &l);
+      if (lane == 0) {
+        st_dev(&a.part[slot].x, m);
+        st_dev(&a.part[slot].y, l);
+      }
+    }
+    KC_T(t2w);
+    KC_TADD(2, t2w - t1);
+  } else {
 #pragma unroll 1
   for (int g = 0; g < G; ++g) {
     const float* zg = sm.z + g * R;
@@ -373,6 +451,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     KC_T(t2c);
     KC_TADD(2, t2c - t2b);
   }
+  }
   KC_T(t3);
 
   // ---------------- 3. the workgroup that completes the unit merges and pulls V
@@ -408,6 +487,104 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   // grouped queries: pull the union of the group's rows once (see pull_union)
   const bool dedup = G > 1 && a.dedup && G * n_eff <= 2 * FT && G * G * n_eff <= 2048 &&
                      s <= 32 * (kFusedZFloats / 2);
+  // Grouped queries, the usual sizes (a head's candidates fit the score buffer, at most 256
+  // rows kept): the heads are merged side by side, one wavefront per head, as many heads per
+  // round as the score buffer holds candidates for.  The workgroup stages the candidates of
+  // a round in LDS with all its threads; from there on a wavefront needs no barrier: the
+  // normaliser from the chunk partials, the selection, the positions of the kept entries,
+  // the lists in global memory and (unless the group's union is pulled) the V pull and sum.
+  if constexpr (G > 1) {
+    constexpr int kWaveKeep = 256;
+    const int fit = M > 0 ? kFusedZFloats / M : 0;
+    const int HR = fit < FW ? (fit < G ? fit : G) : (FW < G ? FW : G);
+    if (HR >= 1 && n_eff <= kWaveKeep) {
+      const int wave = tid >> 6, lane = tid & 63;
+      constexpr int LB = 8;
+#pragma unroll 1
+      for (int g0 = 0; g0 < G; g0 += HR) {
+        const int hr = G - g0 < HR ? G - g0 : HR;
+        const int tot = hr * M;
+        for (int e0 = tid; e0 < tot; e0 += FT * LB) {
+          float zt[LB];
+#pragma unroll
+          for (int u = 0; u < LB; ++u) {
+            const int e = e0 + u * FT;
+            const int h = e / M, i = e - h * M;
+            zt[u] = (e < tot)
+                        ? ld_dev(a.cand_z + (size_t)(unit0 + g0 + h) * a.chunks_cap * kk + i)
+                        : 0.f;
+          }
+#pragma unroll
+          for (int u = 0; u < LB; ++u) {
+            const int e = e0 + u * FT;
+            if (e < tot) sm.z[e] = zt[u];
+          }
+        }
+        __syncthreads();
+        KC_T(w0);
+        if (wave < hr) {
+          const int unit = unit0 + g0 + wave;
+          const size_t slot0 = (size_t)unit * a.chunks_cap;
+          const int32_t* cp = a.cand_pos + slot0 * kk;
+          const float* zl = sm.z + wave * M;
+          float m = -INFINITY, l = 0.f;
+          for (int c = lane; c < chunks_b; c += 64) {
+            const float mc = ld_dev(&a.part[slot0 + c].x), lc = ld_dev(&a.part[slot0 + c].y);
+            const float mm = fmaxf(m, mc);
+            l = (m == mm ? l : l * __expf(m - mm)) + (mc == mm ? lc : lc * __expf(mc - mm));
+            m = mm;
+          }
+          const float mx = wave_max(m);
+          const float inv_Z = 1.f / wave_sum(m == mx ? l : l * __expf(m - mx));
+          float* st_w = reinterpret_cast<float*>(whist + wave * 512);
+          int32_t* st_i = reinterpret_cast<int32_t*>(whist + wave * 512) + kWaveKeep;
+          float kept = 0.f;
+          KC_T(w1);
+          KC_TADD(4, w1 - w0);
+          // (the staging arrays are the selection's histogram, dead by the time it emits)
+          auto cand = [&](int i) { return zl[i]; };
+          float c_lo, c_hi;
+          bool finite;
+          wave_minmax(cand, M, c_lo, c_hi, finite);
+          wave_topn<false>(cand, M, n_eff, c_lo, c_hi, finite, whist + wave * 512,
+                    [&](int r, int i, float v) {
+                      const float w = expf(v - mx) * inv_Z;
+                      kept += w;
+                      st_w[r] = w;
+                      st_i[r] = i;
+                    });
+          const float inv = a.renorm ? 1.f / wave_sum(kept) : 1.f;
+          int32_t* iu = a.idx + (size_t)unit * N;
+          float* wu = a.w + (size_t)unit * N;
+          for (int r = lane; r < n_eff; r += 64) {
+            const int ci = st_i[r];
+            const int32_t t = ((unsigned)ci < (unsigned)M) ? ld_dev(cp + ci) : -1;
+            const float w = a.renorm ? st_w[r] * inv : st_w[r];
+            st_i[r] = t;
+            st_w[r] = w;
+            iu[r] = t;
+            wu[r] = w;
+          }
+          for (int j = n_eff + lane; j < N; j += 64) {
+            iu[j] = -1;
+            wu[j] = 0.f;
+          }
+          KC_T(w2);
+          KC_TADD(5, w2 - w1);
+          if (!dedup)
+            wave_pull<DT, D>(Vp, st_i, st_w, n_eff, s, a.flags, a.out + (size_t)unit * D);
+          KC_T(w3);
+          KC_TADD(6, w3 - w2);
+          KC_TADD(8, 1);
+        }
+        __syncthreads();  // the next round overwrites the staged candidates
+      }
+      if (dedup)
+        pull_union<DT, G, D>(Vp, a.idx + (size_t)unit0 * N, a.w + (size_t)unit0 * N, N, n_eff, s,
+                             a.out + (size_t)unit0 * D, &sm);
+      return;
+    }
+  }
 #pragma unroll 1
   for (int g = 0; g < G; ++g) {
     const int unit = unit0 + g;

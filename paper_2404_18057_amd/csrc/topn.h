@@ -526,4 +526,251 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
   __syncthreads();
 }
 
+// ---- one wavefront selects on its own
+//
+// Exact top-k of keys(0..n-1) by ONE wavefront, ties to the lower index; emit(rank, index,
+// score) as block_topn.  No workgroup barrier anywhere, so the wavefronts of a workgroup can
+// each run it on different data at the same time: a workgroup that has scored G query heads
+// against a chunk of K rows selects for all of them at once instead of head after head (the
+// block-wide routine is bound by its barriers, not by its work).  A wavefront issues one
+// vector instruction every four cycles, so what counts here is instructions per score: four
+// passes over the scores, each a handful of instructions per score.
+//
+// hist: 512 words of LDS owned by the calling wavefront; free for the caller from the first
+// emit on.
+//
+// Usual path (all scores finite): the scores are counted into 512 bins that divide
+// [lo, hi] evenly.  bin(v) = int((v - lo) * 511 / (hi - lo)) never decreases with v
+// (subtraction, multiplication by a positive factor and truncation are monotone in floating
+// point), so the k-th largest score lies in the bin D where the count from the top reaches
+// k, everything in a higher bin is kept and everything in a lower bin is not.  The few scores
+// of bin D (at most 128, else the fallback) are ranked exactly among themselves by (key
+// descending, index ascending); the one whose rank completes k is the threshold, and a final
+// ordered pass keeps key > threshold key, or equal key and index <= threshold index.
+//
+// Fallback (NaN or infinity among the scores, all scores equal, or more than 128 in bin D):
+// radix select on the order-preserving integer keys, 9 bits per pass (bits 31..23, 22..14,
+// 13..5, then the last five): a pass counts the keys that match the prefix found so far,
+// finds the bin of the k-th largest from the top and descends into it; it stops early when
+// every key of that bin is kept; after the last pass the keys equal to the threshold are
+// kept in index order.
+
+// body(score, index, valid) for every index below n rounded up to a multiple of 64, U reads
+// of the wavefront in flight; valid (index < n) is a constant true outside the last batch.
+template <int U, typename Key, typename Body>
+__device__ __forceinline__ void wave_for_each(Key keys, int n, int lane, Body body) {
+  const int n_whole = n - n % (64 * U);
+  int base = 0;
+  for (; base < n_whole; base += 64 * U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = keys(base + u * 64 + lane);
+#pragma unroll
+    for (int u = 0; u < U; ++u) body(v[u], base + u * 64 + lane, true);
+  }
+  if (base < n) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = base + u * 64 + lane;
+      v[u] = i < n ? keys(i) : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = base + u * 64 + lane;
+      if (base + u * 64 < n) body(v[u], i, i < n);   // the same branch in every lane
+    }
+  }
+}
+
+// Count from the top over the 512 bins of hist: the bin where the running count reaches
+// `need`, the count above it, and its own count; the same in every lane.
+__device__ __forceinline__ void wave_find_bin(const uint32_t* hist, int need, int lane, int& bin,
+                                              int& above, int& cnt) {
+  // lane L owns the 8 bins 511 - 8 L ... 504 - 8 L (top down)
+  const uint4* h4 = reinterpret_cast<const uint4*>(hist);
+  const uint4 lo = h4[2 * (63 - lane)], hi = h4[2 * (63 - lane) + 1];
+  const int c[8] = {(int)hi.w, (int)hi.z, (int)hi.y, (int)hi.x,
+                    (int)lo.w, (int)lo.z, (int)lo.y, (int)lo.x};
+  int mine = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) mine += c[j];
+  const int incl = wave_incl_scan(mine, lane);
+  const int above_lane = incl - mine;
+  const bool has = above_lane < need && need <= incl;  // exactly one lane
+  int b = 0, ab = 0, cn = 0;
+  if (has) {
+    int run = above_lane;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (run < need && need <= run + c[j]) {
+        b = 511 - 8 * lane - j;
+        ab = run;
+        cn = c[j];
+      }
+      run += c[j];
+    }
+  }
+  const int src = __builtin_ffsll((long long)__ballot(has)) - 1;
+  bin = __builtin_amdgcn_readlane(b, src);
+  above = __builtin_amdgcn_readlane(ab, src);
+  cnt = __builtin_amdgcn_readlane(cn, src);
+}
+
+__device__ __forceinline__ void wave_zero_hist(uint32_t* hist, int lane) {
+  uint4* h4 = reinterpret_cast<uint4*>(hist);
+  h4[lane] = make_uint4(0, 0, 0, 0);
+  h4[lane + 64] = make_uint4(0, 0, 0, 0);
+}
+
+// lo, hi: smallest and largest score; finite: no NaN or infinity among them (wave_minmax).
+// SUMEXP: also returns the sum of exp(score - hi) over all scores in *sum_exp (added up in
+// the final pass, which visits every score once in any case).
+template <bool SUMEXP, typename Key, typename Emit>
+__device__ __forceinline__ void wave_topn(Key keys, int n, int k, float lo, float hi, bool finite,
+                                          uint32_t* hist, Emit emit, float* sum_exp = nullptr) {
+  constexpr int U = 8, kList = 128;
+  const int lane = threadIdx.x & 63;
+  const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  if (k > n) k = n;
+  // kept: key > T, or key == T and (index <= T_idx, or among the first take_eq such keys when
+  // take_eq >= 0)
+  uint32_t T = 0;
+  int T_idx = 0x7fffffff, take_eq = -1;   // as initialised: everything is kept
+  bool done = k >= n;
+  if (!done && finite && hi > lo) {
+    const float scale = 511.f / (hi - lo);   // 0 if the difference overflows: one bin, fallback
+    auto bin_of = [&](float v) {
+      const int b = (int)((v - lo) * scale);
+      return b > 511 ? 511 : b;
+    };
+    wave_zero_hist(hist, lane);
+    __builtin_amdgcn_wave_barrier();
+    wave_for_each<U>(keys, n, lane, [&](float v, int, bool valid) {
+      if (valid) atomicAdd(&hist[bin_of(v)], 1u);
+    });
+    __builtin_amdgcn_wave_barrier();
+    int D, above, cnt;
+    wave_find_bin(hist, k, lane, D, above, cnt);
+    const int need = k - above;   // 1 <= need <= cnt: how many of bin D are kept
+    if (cnt <= kList) {
+      // the scores of bin D, in any order: key and index; hist[0] counts them
+      uint32_t* l_key = hist + 1;
+      int* l_idx = reinterpret_cast<int*>(hist) + 1 + kList;
+      __builtin_amdgcn_wave_barrier();
+      if (lane == 0) hist[0] = 0;
+      __builtin_amdgcn_wave_barrier();
+      wave_for_each<U>(keys, n, lane, [&](float v, int i, bool valid) {
+        if (valid && bin_of(v) == D) {
+          const uint32_t at = atomicAdd(&hist[0], 1u);
+          if (at < (uint32_t)kList) {   // always: cnt of them exist
+            l_key[at] = score_key(v);
+            l_idx[at] = i;
+          }
+        }
+      });
+      __builtin_amdgcn_wave_barrier();
+      // rank within the list; the entry of rank need - 1 is the threshold
+      uint32_t my_key[2];
+      int my_idx[2], rank[2] = {0, 0};
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int at = lane + 64 * e;
+        my_key[e] = at < cnt ? l_key[at] : 0u;
+        my_idx[e] = at < cnt ? l_idx[at] : 0;
+      }
+      for (int f = 0; f < cnt; ++f) {
+        const uint32_t fk = l_key[f];
+        const int fi = l_idx[f];
+#pragma unroll
+        for (int e = 0; e < 2; ++e)
+          rank[e] += (fk > my_key[e] || (fk == my_key[e] && fi < my_idx[e])) ? 1 : 0;
+      }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        if (lane + 64 * e < cnt && rank[e] == need - 1) {
+          hist[300] = my_key[e];
+          hist[301] = (uint32_t)my_idx[e];
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      T = hist[300];
+      T_idx = (int)hist[301];
+      done = true;
+    }
+  }
+  if (!done) {
+    uint32_t prefix = 0;  // the bits of the threshold found so far
+    int need = k;         // rank of the threshold among the keys that match the prefix
+    int shift = 23;
+#pragma unroll 1
+    for (int pass = 0; pass < 4; ++pass) {
+      const int bits = pass < 3 ? 9 : 5;
+      const uint32_t mask = (1u << bits) - 1u;
+      __builtin_amdgcn_wave_barrier();
+      wave_zero_hist(hist, lane);
+      __builtin_amdgcn_wave_barrier();
+      wave_for_each<U>(keys, n, lane, [&](float v, int, bool valid) {
+        const uint32_t key = score_key(v);
+        const bool match = pass == 0 || (key >> (shift + bits)) == prefix;
+        if (valid && match) atomicAdd(&hist[(key >> shift) & mask], 1u);
+      });
+      __builtin_amdgcn_wave_barrier();
+      int bin, above, cnt;
+      wave_find_bin(hist, need, lane, bin, above, cnt);
+      prefix = (prefix << bits) | ((uint32_t)bin & mask);
+      need -= above;
+      if (cnt == need || pass == 3) {
+        T = shift ? prefix << shift : prefix;   // smallest key with this prefix
+        if (cnt == need) {                      // every key >= T is kept
+          T_idx = 0x7fffffff;
+          take_eq = -1;
+        } else {                                // last pass: keys == T, the first `need`
+          T_idx = -1;
+          take_eq = need;
+        }
+        break;
+      }
+      shift = pass < 2 ? shift - 9 : 0;
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  // ordered compaction: index order is lane order within a step, steps in order
+  int out_pos = 0, eq_seen = 0;
+  float l = 0.f;
+  wave_for_each<U>(keys, n, lane, [&](float v, int i, bool valid) {
+    if (SUMEXP && valid) l += __expf(v - hi);
+    const uint32_t key = score_key(v);
+    bool sel = valid && (key > T || (key == T && i <= T_idx));
+    if (take_eq >= 0) {
+      const bool eq = valid && key == T;
+      const uint64_t eq_b = __ballot(eq);
+      if (eq) sel = eq_seen + __popcll(eq_b & lt_mask) < take_eq;
+      eq_seen += __popcll(eq_b);
+    }
+    const uint64_t sel_b = __ballot(sel);
+    if (sel) emit(out_pos + __popcll(sel_b & lt_mask), i, v);
+    out_pos += __popcll(sel_b);
+  });
+  if (SUMEXP) *sum_exp = wave_sum(l);
+}
+
+// Smallest and largest of keys(0..n-1) and whether all of them are finite, to every lane.
+template <typename Key>
+__device__ __forceinline__ void wave_minmax(Key keys, int n, float& lo, float& hi, bool& finite) {
+  const int lane = threadIdx.x & 63;
+  float a = INFINITY, b = -INFINITY, big = 0.f;
+  wave_for_each<8>(keys, n, lane, [&](float v, int, bool valid) {
+    if (valid) {
+      a = fminf(a, v);
+      b = fmaxf(b, v);
+      big = fmaxf(big, fabsf(v) < INFINITY ? 0.f : 1.f);   // 1 for NaN as well
+    }
+  });
+  lo = wave_min(a);
+  hi = wave_max(b);
+  finite = __ballot(big != 0.f) == 0ull;
+}
+
 }  // namespace kc
