@@ -75,7 +75,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="headline workload of BASELINE.json (1-5); 6 = the shape of "
-                         "the paper's Table 4 headline row (batch 5, 16k context, N 128), for context")
+                         "the paper's Table 4 headline row (batch 5, 16k context, N 128), 7 = grouped queries "
+                         "where the K scan binds (config 3's model, batch 32, 32k context, N 32); both for context")
     ap.add_argument("--only", action="store_true",
                     help="measure the headline workload only (no other workloads, no sweep)")
     ap.add_argument("--layers", type=int, default=0, help="debug: use fewer layers (invalid as a result)")
@@ -367,6 +368,20 @@ def measure(ctx, kc, st, a, probes, dev, headline):
         "frac": gather_gbps / h2d if h2d else None,
         "note": "V-row bytes of a launch / the same launch duration, against the pinned "
                 "host-to-device copy rate measured in this run"}
+    if wl.G > 1 and Lk > 0 and fused_path:
+        # heads of a group that keep the same position: the caches can serve the repeats, so
+        # the link carries between the distinct rows and all rows
+        ix = st.idxs[L - 1].view(wl.B, wl.Hkv, wl.G * wl.N).to(torch.int64)
+        srt = torch.sort(ix, dim=-1).values
+        distinct = ((srt[..., 1:] != srt[..., :-1]) & (srt[..., 1:] >= 0)).sum() + (srt[..., 0] >= 0).sum()
+        kept = (ix >= 0).sum()
+        uf = float(distinct) / max(int(kept), 1)
+        link_part["distinct_row_frac"] = uf
+        link_part["achieved_distinct_rows"] = gather_gbps * uf
+        link_part["frac_distinct_rows"] = gather_gbps * uf / h2d if h2d else None
+        link_part["note"] += ("; distinct_row_frac: distinct positions among the rows the heads of a "
+                              "group keep (last layer of the last step); a repeat may be served by the "
+                              "caches, so the link carried between achieved_distinct_rows and achieved")
     if Lh == L:   # the conventional baseline: the dominant kernel is the K + V stream
         roofline = {"bound": "hbm", "kernel": "full_kernel", "achieved": full_gbps,
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": full_gbps / HBM_PEAK_GBPS,
@@ -470,6 +485,8 @@ def compact(r, spot):
         "bound": bound,
         "frac_of_bound": (rf["frac"] if bound == "hbm" else link.get("frac")),
         "hbm_frac": rf["frac"], "link_frac": link.get("frac"),
+        "distinct_row_frac": link.get("distinct_row_frac"),
+        "link_frac_distinct_rows": link.get("frac_distinct_rows"),
         "step_hbm_frac": rf.get("step", {}).get("hbm_frac"),
         "step_link_frac": rf.get("step", {}).get("link_frac"),
         "binding_note": rf.get("binding_note"),

@@ -75,6 +75,11 @@ CONFIGS = {
     # LLaMA2-7B, 15k prompt + 1k output, batch 5, N = 128), for context only
     6: Workload("table4_llama2_7b_b5_s16384_n128", L=32, B=5, H=32, Hkv=32, S_cap=16384, N=128,
                 dtype="f16", pivot_frac=0.005, seed=1006),
+    # nor this one: grouped queries where the K scan binds (config 3's model at 4 x the
+    # context and a quarter of the kept rows: s / N = 1024), to measure the grouped-query
+    # kernel against the HBM roofline; config 3 itself is bound by the host link
+    7: Workload("gqa4_llama3_8b_b32_s32768_n32", L=32, B=32, H=32, Hkv=8, S_cap=32768, N=32,
+                dtype="bf16", pivot_frac=0.01, seed=1007),
 }
 
 

@@ -33,10 +33,16 @@ namespace {
 
 #ifdef KC_TIMING  // developer build only: per-phase cycle sums in flags[32..]
 #define KC_T(var) const unsigned long long var = wall_clock64()
-#define KC_TADD(slot, val) do { if (threadIdx.x == 0) atomicAdd(reinterpret_cast<unsigned long long*>(a.flags + 32) + (slot), (unsigned long long)(val)); } while (0)
+// the sums of a workgroup are collected in LDS and added to the global slots when it ends, so
+// that no phase waits for a contended global atomic of the phase before it
+#define KC_TDECL __shared__ unsigned long long kc_tacc[9]; if (threadIdx.x == 0) { for (int i_ = 0; i_ < 9; ++i_) kc_tacc[i_] = 0; }
+#define KC_TADD(slot, val) do { if (threadIdx.x == 0) kc_tacc[slot] += (unsigned long long)(val); } while (0)
+#define KC_TFLUSH do { if (threadIdx.x == 0) { for (int i_ = 0; i_ < 9; ++i_) if (kc_tacc[i_]) atomicAdd(reinterpret_cast<unsigned long long*>(a.flags + 32) + i_, kc_tacc[i_]); } } while (0)
 #else
 #define KC_T(var)
+#define KC_TDECL
 #define KC_TADD(slot, val)
+#define KC_TFLUSH
 #endif
 
 constexpr int FT = kFusedThreads;
@@ -358,6 +364,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   if (row0 >= s) return;
   const int chunks_b = (s + R - 1) / R;
   const int n = (s - row0 < R) ? s - row0 : R;  // valid rows of this chunk
+  KC_TDECL
   KC_T(t0);
 
   // ---------------- 1. scores of R positions for the G heads of the group -> LDS
@@ -471,7 +478,10 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   __syncthreads();
   KC_T(t4);
   KC_TADD(3, t4 - t3);
-  if (!sm.last) return;
+  if (!sm.last) {
+    KC_TFLUSH;
+    return;
+  }
 
   const int n_eff = N < s ? N : s;
   const int last_rows = s - (chunks_b - 1) * R;
@@ -582,6 +592,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
       if (dedup)
         pull_union<DT, G, D>(Vp, a.idx + (size_t)unit0 * N, a.w + (size_t)unit0 * N, N, n_eff, s,
                              a.out + (size_t)unit0 * D, &sm);
+      KC_TFLUSH;
       return;
     }
   }
@@ -811,6 +822,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
       pull_union<DT, G, D>(Vp, a.idx + (size_t)unit0 * N, a.w + (size_t)unit0 * N, N, n_eff, s,
                            a.out + (size_t)unit0 * D, &sm);
   }
+  KC_TFLUSH;
 }
 
 // Fills the plan of a launch (see fused_kernel): one workgroup walks the lengths, builds the
