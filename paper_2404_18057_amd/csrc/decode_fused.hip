@@ -497,9 +497,11 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   // grouped queries: pull the union of the group's rows once (see pull_union)
   const bool dedup = G > 1 && a.dedup && G * n_eff <= 2 * FT && G * G * n_eff <= 2048 &&
                      s <= 32 * (kFusedZFloats / 2);
-  // Grouped queries, the usual sizes (a head's candidates fit the score buffer, at most 256
-  // rows kept): the heads are merged side by side, one wavefront per head, as many heads per
-  // round as the score buffer holds candidates for.  The workgroup stages the candidates of
+  // Grouped queries, the usual sizes (the candidates of at least two heads fit the score
+  // buffer, at most 256 rows kept): the heads are merged side by side, one wavefront per head,
+  // as many heads per round as the score buffer holds candidates for.  (One wavefront works
+  // through 1024 candidates in about 5 us, the whole workgroup takes about 10 us for any
+  // number of them: with room for one head at a time the loop below is the faster one.)  The workgroup stages the candidates of
   // a round in LDS with all its threads; from there on a wavefront needs no barrier: the
   // normaliser from the chunk partials, the selection, the positions of the kept entries,
   // the lists in global memory and (unless the group's union is pulled) the V pull and sum.
@@ -507,7 +509,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     constexpr int kWaveKeep = 256;
     const int fit = M > 0 ? kFusedZFloats / M : 0;
     const int HR = fit < FW ? (fit < G ? fit : G) : (FW < G ? FW : G);
-    if (HR >= 1 && n_eff <= kWaveKeep) {
+    if (HR >= 2 && n_eff <= kWaveKeep) {
       const int wave = tid >> 6, lane = tid & 63;
       constexpr int LB = 8;
 #pragma unroll 1
