@@ -59,6 +59,7 @@ struct Smem {
   TopNScratch<FT> sc;
   float red_out[FW * D];
   int last;
+  int redo;  // grouped queries: a head's pruned merge did not fit, merge again without pruning
 };
 
 // V pull + weighted sum for one unit by the whole workgroup: FW * RPL row slots of LPR
@@ -392,7 +393,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   // every candidate below it before selecting.
   const int last_rows_b = s - (chunks_b - 1) * R;
   const int n_full = kk < R ? chunks_b - (last_rows_b > kk ? 0 : 1) : 0;
-  const int r_bound = (G == 1 && n_full > 0 && n > kk) ? (N + n_full - 1) / n_full : 0;
+  const int r_bound = (n_full > 0 && n > kk) ? (N + n_full - 1) / n_full : 0;
   if constexpr (G > 1) {
     // Grouped queries: the G heads are independent, so each wavefront takes a head and does
     // its statistics and its selection alone, without a workgroup barrier, all heads at the
@@ -404,7 +405,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
       const float* zg = sm.z + g * R;
       const size_t slot = (size_t)(unit0 + g) * a.chunks_cap + chunk;
       auto key = [&](int i) { return zg[i]; };
-      float m, z_lo, l;
+      float m, z_lo, l, bound;
       bool finite;
       wave_minmax(key, n, z_lo, m, finite);
       float* cz = a.cand_z + slot * kk;
@@ -413,10 +414,11 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
                       [&](int r, int i, float v) {
                         st_dev(cz + r, v);
                         st_dev(cp + r, row0 + i);
-                      }, &l);
+                      }, &l, r_bound, &bound);
       if (lane == 0) {
         st_dev(&a.part[slot].x, m);
         st_dev(&a.part[slot].y, l);
+        st_dev(a.bound + slot, bound);
       }
     }
     KC_T(t2w);
@@ -474,6 +476,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     const int last = (ticket == chunks_b - 1);
     if (last) st_dev(a.counters + ku, 0);  // ready for the next launch
     sm.last = last;
+    sm.redo = 0;
   }
   __syncthreads();
   KC_T(t4);
@@ -507,6 +510,144 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   // the lists in global memory and (unless the group's union is pulled) the V pull and sum.
   if constexpr (G > 1) {
     constexpr int kWaveKeep = 256;
+    // First choice, pruned as for single heads (see "Pruning bound" above): every wavefront
+    // streams the candidates of its head from memory, keeps those that reach the smallest
+    // bound of the head's full chunks (ordered, with their candidate index) in its 1 / G of
+    // the score buffer, and selects among the survivors, typically a few hundred however
+    // many chunks the unit has; all heads at once.  A head whose survivors do not fit its
+    // part of the buffer (or, with NaN scores, are fewer than the rows to keep) raises
+    // sm.redo and the group is merged again by the paths below.
+    if (n_full > 0 && n_eff <= kWaveKeep && G <= FW) {
+      const int wave = tid >> 6, lane = tid & 63;
+      constexpr int P = kFusedZFloats / G / 2;   // survivors a head may keep
+      if (wave < G) {
+        const int unit = unit0 + wave;
+        const size_t slot0 = (size_t)unit * a.chunks_cap;
+        const float* cz = a.cand_z + slot0 * kk;
+        const int32_t* cp = a.cand_pos + slot0 * kk;
+        float* zreg = sm.z + wave * (2 * P);
+        int32_t* sreg = reinterpret_cast<int32_t*>(zreg) + P;
+        // Every full chunk vouches for r_b of its scores reaching its bound, so the
+        // need-th largest bound, need = ceil(N / r_b) chunks, is a value that N scores of the
+        // unit reach (with more full chunks than rows to keep that is far tighter than the
+        // smallest bound).  Found by bisection on the integer keys of up to 8 bounds a lane.
+        constexpr int PBL = 8;
+        const int r_b = (N + n_full - 1) / n_full, need = (N + r_b - 1) / r_b;
+        const int pbn = (chunks_b + 63) / 64;
+        float m = -INFINITY, l = 0.f, pb = INFINITY;
+        uint32_t pk[PBL];
+#pragma unroll
+        for (int j = 0; j < PBL; ++j) pk[j] = 0u;   // below every key of a real bound
+        for (int c = lane, j = 0; c < chunks_b; c += 64, ++j) {
+          const float mc = ld_dev(&a.part[slot0 + c].x), lc = ld_dev(&a.part[slot0 + c].y);
+          const float mm = fmaxf(m, mc);
+          l = (m == mm ? l : l * __expf(m - mm)) + (mc == mm ? lc : lc * __expf(mc - mm));
+          m = mm;
+          if (c < chunks_b - 1 || last_rows > kk) {
+            const float bc = ld_dev(a.bound + slot0 + c);
+            pb = fminf(pb, bc);
+#pragma unroll
+            for (int jj = 0; jj < PBL; ++jj)
+              if (jj == j) pk[jj] = score_key(bc);
+          }
+        }
+        const float mx = wave_max(m);
+        const float inv_Z = 1.f / wave_sum(m == mx ? l : l * __expf(m - mx));
+        float L = wave_min(pb);   // the smallest bound: always valid
+        if (pbn <= PBL && need < n_full) {
+          uint32_t T = 0u;
+#pragma unroll 1
+          for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t cand_key = T | (1u << bit);
+            int cnt = 0;
+#pragma unroll
+            for (int j = 0; j < PBL; ++j)
+              if (j < pbn) cnt += pk[j] >= cand_key ? 1 : 0;
+            if (wave_sum(cnt) >= need) T = cand_key;
+          }
+          // T is the need-th largest key; the bound it belongs to is the smallest one not below
+          float at = INFINITY;
+          for (int c = lane; c < chunks_b; c += 64)
+            if (c < chunks_b - 1 || last_rows > kk) {
+              const float bc = ld_dev(a.bound + slot0 + c);
+              if (score_key(bc) >= T) at = fminf(at, bc);
+            }
+          at = wave_min(at);
+          if (at < INFINITY && at > L) L = at;
+        }
+        if (!(L > -INFINITY)) L = -INFINITY;   // NaN or -inf: keep everything
+        const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+        constexpr int LB = 16;
+        int Mp = 0;
+        bool fits = true;
+        for (int i0 = 0; i0 < M && fits; i0 += 64 * LB) {
+          float zt[LB];
+#pragma unroll
+          for (int u = 0; u < LB; ++u) {
+            const int i = i0 + u * 64 + lane;
+            zt[u] = (i < M) ? ld_dev(cz + i) : -INFINITY;
+          }
+#pragma unroll
+          for (int u = 0; u < LB; ++u) {
+            const int i = i0 + u * 64 + lane;
+            const bool keep = i < M && zt[u] >= L;
+            const uint64_t b = __ballot(keep);
+            const int cnt = __popcll(b);
+            if (Mp + cnt > P) fits = false;   // the same in every lane
+            if (keep && fits) {
+              const int dst = Mp + __popcll(b & lt_mask);
+              zreg[dst] = zt[u];
+              sreg[dst] = i;
+            }
+            Mp += cnt;
+          }
+        }
+        if (!fits || Mp < n_eff) {
+          if (lane == 0) sm.redo = 1;
+        } else {
+          auto cand = [&](int i) { return zreg[i]; };
+          float c_lo, c_hi;
+          bool finite;
+          wave_minmax(cand, Mp, c_lo, c_hi, finite);
+          float* st_w = reinterpret_cast<float*>(whist + wave * 512);
+          int32_t* st_i = reinterpret_cast<int32_t*>(whist + wave * 512) + kWaveKeep;
+          float kept = 0.f;
+          wave_topn<false>(cand, Mp, n_eff, c_lo, c_hi, finite, whist + wave * 512,
+                           [&](int r, int i, float v) {
+                             const float w = expf(v - mx) * inv_Z;
+                             kept += w;
+                             st_w[r] = w;
+                             st_i[r] = sreg[i];
+                           });
+          const float inv = a.renorm ? 1.f / wave_sum(kept) : 1.f;
+          int32_t* iu = a.idx + (size_t)unit * N;
+          float* wu = a.w + (size_t)unit * N;
+          for (int r = lane; r < n_eff; r += 64) {
+            const int ci = st_i[r];
+            const int32_t t = ((unsigned)ci < (unsigned)M) ? ld_dev(cp + ci) : -1;
+            const float w = a.renorm ? st_w[r] * inv : st_w[r];
+            st_i[r] = t;
+            st_w[r] = w;
+            iu[r] = t;
+            wu[r] = w;
+          }
+          for (int j = n_eff + lane; j < N; j += 64) {
+            iu[j] = -1;
+            wu[j] = 0.f;
+          }
+          if (!dedup)
+            wave_pull<DT, D>(Vp, st_i, st_w, n_eff, s, a.flags, a.out + (size_t)unit * D);
+        }
+      }
+      __syncthreads();
+      if (!sm.redo) {
+        if (dedup)
+          pull_union<DT, G, D>(Vp, a.idx + (size_t)unit0 * N, a.w + (size_t)unit0 * N, N, n_eff,
+                               s, a.out + (size_t)unit0 * D, &sm);
+        KC_TFLUSH;
+        return;
+      }
+    }
     const int fit = M > 0 ? kFusedZFloats / M : 0;
     const int HR = fit < FW ? (fit < G ? fit : G) : (FW < G ? FW : G);
     if (HR >= 2 && n_eff <= kWaveKeep) {

@@ -626,9 +626,14 @@ __device__ __forceinline__ void wave_zero_hist(uint32_t* hist, int lane) {
 // lo, hi: smallest and largest score; finite: no NaN or infinity among them (wave_minmax).
 // SUMEXP: also returns the sum of exp(score - hi) over all scores in *sum_exp (added up in
 // the final pass, which visits every score once in any case).
+// r2 / bound (optional): *bound receives a value that at least r2 of the scores reach (one
+// bin width below the lower edge of the bin that holds the r2-th largest: a score in that bin
+// or above has (v - lo) * scale >= its bin number up to two roundings, far less than the one
+// bin of slack), -inf when no histogram over [lo, hi] is built.
 template <bool SUMEXP, typename Key, typename Emit>
 __device__ __forceinline__ void wave_topn(Key keys, int n, int k, float lo, float hi, bool finite,
-                                          uint32_t* hist, Emit emit, float* sum_exp = nullptr) {
+                                          uint32_t* hist, Emit emit, float* sum_exp = nullptr,
+                                          int r2 = 0, float* bound = nullptr) {
   constexpr int U = 8, kList = 128;
   const int lane = threadIdx.x & 63;
   const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
@@ -638,6 +643,7 @@ __device__ __forceinline__ void wave_topn(Key keys, int n, int k, float lo, floa
   uint32_t T = 0;
   int T_idx = 0x7fffffff, take_eq = -1;   // as initialised: everything is kept
   bool done = k >= n;
+  float bound_v = -INFINITY;
   if (!done && finite && hi > lo) {
     const float scale = 511.f / (hi - lo);   // 0 if the difference overflows: one bin, fallback
     auto bin_of = [&](float v) {
@@ -652,6 +658,11 @@ __device__ __forceinline__ void wave_topn(Key keys, int n, int k, float lo, floa
     __builtin_amdgcn_wave_barrier();
     int D, above, cnt;
     wave_find_bin(hist, k, lane, D, above, cnt);
+    if (r2 > 0) {
+      int D2, above2, cnt2;
+      wave_find_bin(hist, r2 < n ? r2 : n, lane, D2, above2, cnt2);
+      bound_v = D2 > 0 ? lo + (float)(D2 - 1) / scale : -INFINITY;
+    }
     const int need = k - above;   // 1 <= need <= cnt: how many of bin D are kept
     if (cnt <= kList) {
       // the scores of bin D, in any order: key and index; hist[0] counts them
@@ -754,6 +765,7 @@ __device__ __forceinline__ void wave_topn(Key keys, int n, int k, float lo, floa
     out_pos += __popcll(sel_b);
   });
   if (SUMEXP) *sum_exp = wave_sum(l);
+  if (bound) *bound = bound_v;
 }
 
 // Smallest and largest of keys(0..n-1) and whether all of them are finite, to every lane.
