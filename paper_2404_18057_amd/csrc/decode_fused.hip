@@ -168,6 +168,36 @@ __device__ __forceinline__ void wave_pull(const uint4* __restrict__ Vp, const in
   }
 }
 
+// What the wavefront that has selected a head's rows does next: st_w[r] / st_i[r] hold the
+// weight and the candidate index of the r-th kept entry (LDS), kept this lane's share of the
+// weights' sum.  Fetches the candidates' positions in one batch, renormalises if asked,
+// writes the unit's lists and, unless the group's union is pulled afterwards, pulls and sums
+// its V rows.
+template <int DT, int D>
+__device__ __forceinline__ void wave_finish_head(const FusedArgs& a, int unit, int N, int n_eff,
+                                                 int M, int s, const int32_t* cp, float* st_w,
+                                                 int32_t* st_i, float kept, bool dedup,
+                                                 const uint4* __restrict__ Vp) {
+  const int lane = threadIdx.x & 63;
+  const float inv = a.renorm ? 1.f / wave_sum(kept) : 1.f;
+  int32_t* iu = a.idx + (size_t)unit * N;
+  float* wu = a.w + (size_t)unit * N;
+  for (int r = lane; r < n_eff; r += 64) {
+    const int ci = st_i[r];
+    const int32_t t = ((unsigned)ci < (unsigned)M) ? ld_dev(cp + ci) : -1;
+    const float w = a.renorm ? st_w[r] * inv : st_w[r];
+    st_i[r] = t;
+    st_w[r] = w;
+    iu[r] = t;
+    wu[r] = w;
+  }
+  for (int j = n_eff + lane; j < N; j += 64) {
+    iu[j] = -1;
+    wu[j] = 0.f;
+  }
+  if (!dedup) wave_pull<DT, D>(Vp, st_i, st_w, n_eff, s, a.flags, a.out + (size_t)unit * D);
+}
+
 // De-duplicated V pull for a group of G query heads (grouped-query attention): the heads
 // of a group read the same V head, so a position that several of them selected is pulled
 // over the host link once and accumulated into each head's output with that head's weight.
@@ -382,6 +412,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
   KC_TADD(7, 1);
 
   // ---------------- 2. per head: softmax partials and the chunk's own top-min(N, R)
+  const bool lone = G == 1 && (long long)a.kv_count * a.chunks_cap <= 512;
   float* const stage_f = reinterpret_cast<float*>(sm.sc.hist);
   int32_t* const stage_i = reinterpret_cast<int32_t*>(sm.sc.hist) + kStage;
   const int k_loc = kk < n ? kk : n;
@@ -423,6 +454,29 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
     }
     KC_T(t2w);
     KC_TADD(2, t2w - t1);
+  } else if (lone) {
+    // a launch of a single round of workgroups is bound by the latency of its steps, not by
+    // HBM: the first wavefront selects alone (no barriers; 2-3 us instead of 7), the others
+    // go on to the hand-over barrier
+    if (tid < 64) {
+      const size_t slot = (size_t)unit0 * a.chunks_cap + chunk;
+      auto key = [&](int i) { return sm.z[i]; };
+      float m, z_lo, l, bound;
+      bool finite;
+      wave_minmax(key, n, z_lo, m, finite);
+      float* cz = a.cand_z + slot * kk;
+      int32_t* cp = a.cand_pos + slot * kk;
+      wave_topn<true>(key, n, k_loc, z_lo, m, finite, sm.sc.hist,
+                      [&](int r, int i, float v) {
+                        st_dev(cz + r, v);
+                        st_dev(cp + r, row0 + i);
+                      }, &l, r_bound, &bound);
+      if (tid == 0) {
+        st_dev(&a.part[slot].x, m);
+        st_dev(&a.part[slot].y, l);
+        st_dev(a.bound + slot, bound);
+      }
+    }
   } else {
 #pragma unroll 1
   for (int g = 0; g < G; ++g) {
@@ -619,24 +673,7 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
                              st_w[r] = w;
                              st_i[r] = sreg[i];
                            });
-          const float inv = a.renorm ? 1.f / wave_sum(kept) : 1.f;
-          int32_t* iu = a.idx + (size_t)unit * N;
-          float* wu = a.w + (size_t)unit * N;
-          for (int r = lane; r < n_eff; r += 64) {
-            const int ci = st_i[r];
-            const int32_t t = ((unsigned)ci < (unsigned)M) ? ld_dev(cp + ci) : -1;
-            const float w = a.renorm ? st_w[r] * inv : st_w[r];
-            st_i[r] = t;
-            st_w[r] = w;
-            iu[r] = t;
-            wu[r] = w;
-          }
-          for (int j = n_eff + lane; j < N; j += 64) {
-            iu[j] = -1;
-            wu[j] = 0.f;
-          }
-          if (!dedup)
-            wave_pull<DT, D>(Vp, st_i, st_w, n_eff, s, a.flags, a.out + (size_t)unit * D);
+          wave_finish_head<DT, D>(a, unit, N, n_eff, M, s, cp, st_w, st_i, kept, dedup, Vp);
         }
       }
       __syncthreads();
@@ -706,26 +743,9 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
                       st_w[r] = w;
                       st_i[r] = i;
                     });
-          const float inv = a.renorm ? 1.f / wave_sum(kept) : 1.f;
-          int32_t* iu = a.idx + (size_t)unit * N;
-          float* wu = a.w + (size_t)unit * N;
-          for (int r = lane; r < n_eff; r += 64) {
-            const int ci = st_i[r];
-            const int32_t t = ((unsigned)ci < (unsigned)M) ? ld_dev(cp + ci) : -1;
-            const float w = a.renorm ? st_w[r] * inv : st_w[r];
-            st_i[r] = t;
-            st_w[r] = w;
-            iu[r] = t;
-            wu[r] = w;
-          }
-          for (int j = n_eff + lane; j < N; j += 64) {
-            iu[j] = -1;
-            wu[j] = 0.f;
-          }
           KC_T(w2);
           KC_TADD(5, w2 - w1);
-          if (!dedup)
-            wave_pull<DT, D>(Vp, st_i, st_w, n_eff, s, a.flags, a.out + (size_t)unit * D);
+          wave_finish_head<DT, D>(a, unit, N, n_eff, M, s, cp, st_w, st_i, kept, dedup, Vp);
           KC_T(w3);
           KC_TADD(6, w3 - w2);
           KC_TADD(8, 1);
@@ -913,7 +933,16 @@ __global__ __launch_bounds__(FT) __attribute__((amdgpu_waves_per_eu(4, 4))) void
         iu[r] = pos_here ? pos_l[i] : ld_dev(cp + ci);
       }
     };
-    if (pruned || z_in_lds)
+    if (lone && stage_out && (pruned || z_in_lds)) {
+      if (tid < 64) {
+        auto cand = [&](int i) { return sm.z[i]; };
+        float c_lo, c_hi;
+        bool finite;
+        wave_minmax(cand, Mp, c_lo, c_hi, finite);
+        wave_topn<false>(cand, Mp, n_eff, c_lo, c_hi, finite, sm.sc.hist, emit);
+      }
+      __syncthreads();
+    } else if (pruned || z_in_lds)
       block_topn<FT, true>([&](int i) { return sm.z[i]; }, Mp, n_eff, &sm.sc, emit);
     else  // more candidates than the LDS buffer holds: read them around the L2 every pass
       block_topn<FT, true>([&](int i) { return ld_dev(cz + i); }, M, n_eff, &sm.sc, emit);
