@@ -561,6 +561,17 @@ def main():
             others[w2.name] = ent
             s2.release()
         result["workloads"] = others
+        # not one of the named workloads: grouped queries where the K scan binds (the named
+        # grouped-query workload, config 3, is bound by the host link), so that the line also
+        # holds the grouped-query kernel against the HBM roofline
+        w7 = ki.config(7)
+        t0 = time.time()
+        s7 = Workload(ctx, kc, w7, w7.L, 0, pool, dev)
+        r7 = measure(ctx, kc, s7, a, probes, dev, headline=False)
+        ent = compact(r7, spot_check(w7, w7.L, s7.outs, s7.idxs, s7.ws, 16))
+        ent["wall_s"] = round(time.time() - t0, 1)
+        result["context_workloads"] = {w7.name: ent}
+        s7.release()
         result["probes"] = dict(probes)
     print(json.dumps(result))
 
