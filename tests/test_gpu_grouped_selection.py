@@ -82,6 +82,29 @@ def test_random_scores_with_repeated_rows(kc, ctx, G, S, N):
         check_manual(res, lens, N, G=G)
 
 
+@pytest.mark.parametrize("G,S,N,rows", [(4, 70000, 16, 512), (4, 70000, 200, 512), (8, 70000, 40, 512),
+                                        (4, 300000, 24, 512), (2, 150000, 256, 1024)])
+def test_many_chunks_per_unit(kc, ctx, G, S, N, rows):
+    """Small chunks forced on long contexts: 137, 586 and 147 chunks per unit, i.e. more chunks
+    than rows to keep (the unit's pruning bound is then the N-th largest chunk bound, found over
+    several bounds per lane, or the smallest one beyond 512 chunks) and fewer (the smallest
+    bound).  Repeated rows put exact ties among the candidates."""
+    rng = np.random.default_rng(S + N + G)
+    B, Hkv, d = 1, 2, 128
+    q = rng.standard_normal((B, Hkv * G, d))
+    K = rng.standard_normal((B, Hkv, S, d)).astype(np.float32)
+    src = rng.integers(0, S, size=300)
+    dst = rng.integers(0, S, size=300)
+    K[:, :, dst] = K[:, :, src]
+    V = rng.standard_normal((B, Hkv, S, d)).astype(np.float32)
+    ctx.set_fused_rows(rows)
+    try:
+        res = manual_case(kc, ctx, q, K, V, [S], N)
+    finally:
+        ctx.set_fused_rows(0)
+    check_manual(res, [S], N, G=G)
+
+
 def test_renormalised_weights_in_groups(kc, ctx):
     rng = np.random.default_rng(5)
     B, Hkv, G, S, d, N = 2, 2, 4, 7000, 128, 48
