@@ -25,6 +25,11 @@
 //
 // Units finish at different times (chunks of one unit are adjacent in the
 // grid), so the V pulls of early units overlap the K scan of later ones.
+//
+// Steps 2 and 3 are done by the whole workgroup for a single query head (block_topn,
+// pull_and_accumulate) and by one wavefront per head, all heads of a group at the same
+// time, for grouped queries (wave_topn, wave_pull); a launch of a single round of workgroups
+// uses the single-wavefront routines for a single head as well (see the kernel body).
 #include "attn_common.h"
 #include "topn.h"
 

@@ -20,6 +20,10 @@
 //
 // Scores are read through a caller-supplied accessor keys(i), so they can live
 // in LDS, in global memory, or behind a cache-bypassing load.
+//
+// The second half of the file holds the same selection for ONE wavefront (wave_topn, no
+// workgroup barrier: several heads of a query group are selected at the same time by
+// different wavefronts); it orders entries the same way and is described there.
 #pragma once
 
 #include <hip/hip_runtime.h>
