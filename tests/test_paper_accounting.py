@@ -123,3 +123,15 @@ def test_measured_sweep_shows_the_trend_of_table_4():
         by_n = {c["N"]: c["us"] for c in cells}
         assert abs(by_n[512] / by_n[256] - 2.0) < 0.2               # proportional to N
         assert cells[-1]["tps"] < 0.25 * cells[0]["tps"]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the bench contract of this build: one GPU; a request for more exits with a message
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr + r.stdout
+    assert not r.stdout.strip().startswith("{")
