@@ -52,11 +52,14 @@ def algorithmic_bytes(wl, lens, k_elem_bytes=2, N=None):
     return k_bytes, v_bytes
 
 
-def eq4_break_even(bw_gpu, bw_h2d, overlapped=False):
+def eq4_break_even(bw_gpu, bw_h2d, overlapped=False, G=1):
     """s/N above which KCache is no slower than a conventional KV cache (section 3.2,
     equation (4)): Bandwidth_GPU / Bandwidth_H2D when the V pull follows the K scan; half of
-    it when the two overlap (N rows over the link then only have to beat 2 s rows from HBM)."""
-    return bw_gpu / bw_h2d / (2.0 if overlapped else 1.0)
+    it when the two overlap (N rows over the link then only have to beat 2 s rows from HBM).
+    G query heads per KV head (the paper writes the condition for G = 1): the HBM side reads a
+    position once per group while every query head pulls its own N rows, so the ratio grows
+    G-fold."""
+    return G * bw_gpu / bw_h2d / (2.0 if overlapped else 1.0)
 
 
 def launch_floor_us(wl, lens, N, hbm_gbps, link_gbps, k_elem_bytes=2):
@@ -784,7 +787,9 @@ def crossover_leg(ctx, kc, wl, cache, q, dev, probes, reps=10):
             "break_even_s_over_N": wins,
             "eq4_ratio_measured_bandwidths": eq4_break_even(hbm, link) if hbm and link else None,
             "eq4_ratio_with_overlap": (eq4_break_even(hbm, link, overlapped=True)
-                                       if hbm and link else None)}
+                                       if hbm and link else None),
+            "eq4_ratio_with_overlap_for_this_group_size": (
+                eq4_break_even(hbm, link, overlapped=True, G=wl.G) if hbm and link else None)}
 
 
 def pick_units(wl, L, n_units):

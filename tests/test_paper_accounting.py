@@ -72,6 +72,23 @@ def test_break_even_formula_reproduces_the_papers_a100_example():
                                 overlapped=True) == r / 2
 
 
+def test_break_even_for_groups_follows_from_the_byte_counts():
+    # with G query heads per KV head the launch floors of the accounting cross at G times the
+    # single-head ratio: K and V of a position are read from HBM once per group, the N rows of
+    # V cross the link once per query head
+    hbm, link = 7000.0, 55.0
+    for G in (1, 4, 8):
+        wl = ki.config(3).replace(H=8 * G, Hkv=8, B=4, S_cap=1 << 20, len_range=None)
+        N = 64
+        ratio = bench.eq4_break_even(hbm, link, overlapped=True, G=G)
+        for s, kcache_wins in ((int(0.9 * ratio * N), False), (int(1.1 * ratio * N), True)):
+            lens = np.full(wl.B, s, dtype=np.int32)
+            k_bytes, v_bytes = bench.algorithmic_bytes(wl, lens, N=N)
+            t_kcache = max(k_bytes / hbm, v_bytes / link)      # the two transfers overlap
+            t_conventional = 2 * k_bytes / hbm                  # K and V rows from HBM
+            assert (t_kcache <= t_conventional) == kcache_wins, (G, s)
+
+
 def read_sweep():
     """Rows of the tracked config-4 sweep (profiles/config4_sweep.md): measured on the MI355X."""
     path = os.path.join(os.path.dirname(GOLDEN), "..", "profiles", "config4_sweep.md")
