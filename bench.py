@@ -486,7 +486,10 @@ def compact(r, spot):
         "k_bytes_per_launch": rf["bytes_per_launch"],
         "K_GBps_per_launch": rf["achieved"], "V_row_GBps_per_launch": link.get("achieved"),
         "bound": bound,
-        "frac_of_bound": (rf["frac"] if bound == "hbm" else link.get("frac")),
+        # grouped queries: the link carried at least the distinct rows of every group (a repeat
+        # may come from the caches), so the lower bound is the figure that cannot overstate
+        "frac_of_bound": (rf["frac"] if bound == "hbm" else
+                          link.get("frac_distinct_rows") or link.get("frac")),
         "hbm_frac": rf["frac"], "link_frac": link.get("frac"),
         "distinct_row_frac": link.get("distinct_row_frac"),
         "link_frac_distinct_rows": link.get("frac_distinct_rows"),
