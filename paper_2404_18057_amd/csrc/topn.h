@@ -519,8 +519,8 @@ __device__ __forceinline__ void block_topn(Key keys, int n, int k, TopNScratch<N
         sel = gt || (eq && i <= T_idx);
       } else {
         const uint64_t eq_b = __ballot(eq);
-        sel = gt || (eq && (eq_before + __popcll(eq_b & lt_mask)) < take_eq);
-        eq_before += __popcll(eq_b);
+        sel = gt || (eq && (eq_before + (int)__popcll(eq_b & lt_mask)) < take_eq);
+        eq_before += (int)__popcll(eq_b);
       }
       const uint64_t sel_b = __ballot(sel);
       if (sel) emit(out_pos + __popcll(sel_b & lt_mask), i, v);
@@ -761,8 +761,8 @@ __device__ __forceinline__ void wave_topn(Key keys, int n, int k, float lo, floa
     if (take_eq >= 0) {
       const bool eq = valid && key == T;
       const uint64_t eq_b = __ballot(eq);
-      if (eq) sel = eq_seen + __popcll(eq_b & lt_mask) < take_eq;
-      eq_seen += __popcll(eq_b);
+      if (eq) sel = eq_seen + (int)__popcll(eq_b & lt_mask) < take_eq;
+      eq_seen += (int)__popcll(eq_b);
     }
     const uint64_t sel_b = __ballot(sel);
     if (sel) emit(out_pos + __popcll(sel_b & lt_mask), i, v);
